@@ -1,0 +1,150 @@
+/*
+ * rsa.h -- C-ABI of librsa.so: rectified block-sparse self-attention of a video DiT
+ * (Rectified SpaAttn, arXiv 2511.19835) for one AMD MI355X (gfx950).
+ *
+ * One attention layer is three calls on one HIP stream, with no host synchronisation
+ * in between (paper Alg. 1):
+ *
+ *   rsa_pool                   steps 1-11   pooling, implicit full attention (IPAR),
+ *                                           compensation mask (GAPR)
+ *   rsa_select_blocks          steps 13-14, 19   sparse mask, block lists, factor R
+ *   rsa_sparse_attn_rectified  steps 16-23  block-sparse attention + rectification
+ *
+ * Conventions for every entry point
+ *   - All tensor pointers are DEVICE pointers owned by the caller. The library never
+ *     allocates, frees or synchronises; all work is enqueued on `stream` (a hipStream_t
+ *     passed as void*; NULL is the default stream). Outputs are fully overwritten.
+ *   - Q, K, V, O are bf16, token order [video | text] (Alg. 1 steps 1-2, 23), addressed as
+ *     ptr[b*stride_b + h*stride_h + t*stride_t + c], c < head_dim contiguous. Strides are
+ *     in elements and must be multiples of 8 (16-byte rows).
+ *   - Blocks (Sec. 3.1): B = B^q = B^k = `block`. Video block m < N covers tokens
+ *     [m*B, min((m+1)*B, T_v)); text block N+i covers [T_v + i*B, min(T_v + (i+1)*B, T)).
+ *     N = ceil(T_v/B), M = N + ceil(T_t/B). Text always starts a block of its own (isolated
+ *     pooling, Sec. 4.1); the last video and last text block may be ragged. Query blocks use
+ *     the same partition: blocks n < N are the sparse rows, text query blocks run dense.
+ *   - Pooled/score tensors are fp32, contiguous, batch-major then head-major:
+ *     [batch][heads][...].  W = ceil(M/32) 32-bit words per bit-mask row, bit (m % 32) of
+ *     word (m / 32) is block m; bits at m >= M are zero.
+ *   - Return value: RSA_OK or a negative RSA_E_* code. Arguments are validated on the host
+ *     before anything is launched; on error nothing has been enqueued. No exceptions, no exit.
+ *   - Results are deterministic (no atomics on any output path).
+ */
+#ifndef RSA_H
+#define RSA_H
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+enum {
+  RSA_OK = 0,
+  RSA_E_NULL = -1,        /* a required pointer is NULL */
+  RSA_E_SHAPE = -2,       /* non-positive sizes, misaligned strides */
+  RSA_E_UNSUPPORTED = -3, /* head_dim or block outside {64,128}, M > RSA_MAX_BLOCKS */
+  RSA_E_WORKSPACE = -4,   /* workspace smaller than rsa_workspace_bytes says */
+  RSA_E_RANGE = -5,       /* sparsity / p / mode / flags out of range */
+  RSA_E_LAUNCH = -6       /* the HIP runtime refused a launch */
+};
+
+#define RSA_MAX_BLOCKS 4096 /* largest M = key blocks per (batch, head) */
+
+/* Problem statement of Alg. 1 ("Require": Q, K, V, T_v, T_t) plus the block size of Sec. 3.1. */
+typedef struct rsa_shape {
+  int32_t batch;     /* >= 1 */
+  int32_t heads;     /* >= 1 */
+  int32_t head_dim;  /* d: 64 or 128 */
+  int32_t block;     /* B: 64 or 128 */
+  int64_t t_video;   /* T_v >= 1 */
+  int64_t t_text;    /* T_t >= 0 */
+  int64_t stride_b, stride_h, stride_t; /* element strides of Q, K, V and O */
+  float scale;       /* softmax scale; 0 selects 1/sqrt(d) (Sec. 3.1) */
+} rsa_shape;
+
+/* rsa_sparse_attn_rectified flags */
+#define RSA_RECTIFY_CRITICAL 1 /* multiply video rows by R_n      (Alg. 1 step 20) */
+#define RSA_COMPENSATE 2       /* add the pooled non-critical term (Alg. 1 steps 21-22) */
+#define RSA_DENSE 4            /* ignore lists: every query block attends to all M blocks,
+                                  no rectification (full attention, Sec. 3.1) */
+
+/* Host only. N (video blocks), M (all key blocks) and W (mask words per row) for a shape. */
+int rsa_block_counts(const rsa_shape* shape, int64_t* n_video_blocks, int64_t* n_blocks,
+                     int64_t* mask_words);
+
+/* Host only. Bytes of device scratch rsa_pool and rsa_sparse_attn_rectified need. */
+int rsa_workspace_bytes(const rsa_shape* shape, size_t* pool_ws_bytes, size_t* attn_ws_bytes);
+
+/*
+ * Alg. 1 steps 1-11.
+ *   Qp  [b][h][N][d]  block means of the video queries      (Sec. 3.2 pooled equations)
+ *   Kp  [b][h][M][d]  block means of all key blocks; a text block's mean is only used by
+ *                     the gain/error gate, never by the implicit attention
+ *   Vp  [b][h][M][d]  block means of V                      (Alg. 1 step 3)
+ *   Vt  [b][h][M][d][B] bf16: V of each key block stored channel-major so the P.V product
+ *                     reads it like K; tokens past the end of a ragged block are zero.
+ *                     Within every run of 16 tokens the two middle groups of four are
+ *                     swapped (order 0-3, 8-11, 4-7, 12-15). Opaque to callers: pass it on
+ *                     to rsa_sparse_attn_rectified.
+ *   Spool [b][h][N][M] raw pooled scores  s^pool = q^pool . k^pool * scale   (Sec. 3.2)
+ *   Lmass [b][h][N][M] block log-mass: s^pool + ln(c_m) for a video block (c_m = tokens in
+ *                     the block), log-sum-exp over the block's individual token scores
+ *                     q^pool . k_t * scale for a text block (Sec. 4.1, isolated pooling)
+ *   Apool [b][h][N][M] implicit full attention A^pool = row-softmax(Lmass); equal to the
+ *                     paper's reallocation: video block weights times block size, text
+ *                     token weights summed per block, renormalised (Sec. 4.1)
+ *   Mc_bits [b][h][N][W] compensation mask M_c (Sec. 4.2). gapr_mode 0: all zero;
+ *                     2: all ones; 1: bit set iff  |s^pool| > DA + DB  with
+ *                     DA = mean_i |(q_i - q^pool_n).k^pool_m| * scale and
+ *                     DB = mean_j |q^pool_n.(k_j - k^pool_m)| * scale, i.e. the gain
+ *                     |sum_ij s^pool| exceeds the first-order pooling error with the
+ *                     absolute value taken per term (the printed signed sum vanishes).
+ *   ws / ws_bytes     device scratch, at least pool_ws_bytes, 256-byte aligned.
+ */
+int rsa_pool(const rsa_shape* shape, const void* Q, const void* K, const void* V,
+             float* Qp, float* Kp, float* Vp, void* Vt,
+             float* Spool, float* Apool, float* Lmass, uint32_t* Mc_bits, int gapr_mode,
+             void* ws, size_t ws_bytes, void* stream);
+
+/*
+ * Alg. 1 steps 13-14 and 19, per video query block n:
+ *   keep the k = clamp(M - floor(sparsity*M + 1e-6), 1, M) blocks of largest Lmass (equal
+ *   keys: lower block index first); if p > 0 extend, in the same descending order, until
+ *   the kept A^pool weight exceeds p; OR with forced_bits (the adjacency mask M_adja,
+ *   [b][h][N][W], may be NULL).
+ *   mask_bits [b][h][N][W]  the sparse mask
+ *   block_idx [b][h][N][M]  kept block indices, ascending, first count[n] entries valid
+ *   count     [b][h][N]
+ *   R         [b][h][N]     rectification factor: sum of A^pool over kept blocks (Sec. 4.1)
+ * sparsity in [0,1], p in [0,1].
+ */
+int rsa_select_blocks(const rsa_shape* shape, const float* Lmass, const float* Apool,
+                      double sparsity, double p, const uint32_t* forced_bits,
+                      uint32_t* mask_bits, int32_t* block_idx, int32_t* count, float* R,
+                      void* stream);
+
+/*
+ * Alg. 1 steps 16-23. For video query block n: online-softmax attention of its tokens over
+ * the tokens of the blocks in block_idx[n][0..count[n]) only (masked keys are excluded from
+ * the softmax, Sec. 3.1), times R[n] (RSA_RECTIFY_CRITICAL), plus
+ * sum_{m: not mask and M_c} Apool[n][m] * Vp[m] (RSA_COMPENSATE). Text query blocks: full
+ * attention over all tokens. O has the layout of Q. `lse` (nullable, [b][h][T] fp32)
+ * receives the natural-log softmax denominator (including the row maximum) of the
+ * un-rectified sparse/dense attention of every row.
+ * With RSA_DENSE every list/mask/R/Apool/Mc/Vp pointer may be NULL.
+ * ws / ws_bytes: device scratch of at least attn_ws_bytes (may be NULL when that is 0).
+ */
+int rsa_sparse_attn_rectified(const rsa_shape* shape, const void* Q, const void* K, const void* Vt,
+                              const int32_t* block_idx, const int32_t* count,
+                              const uint32_t* mask_bits, const float* R, const float* Apool,
+                              const uint32_t* Mc_bits, const float* Vp, int flags,
+                              void* O, float* lse, void* ws, size_t ws_bytes, void* stream);
+
+/* Static string for a return code. */
+const char* rsa_status_string(int status);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* RSA_H */

@@ -1,0 +1,152 @@
+// Uniform block pooling of Q, K, V (paper Sec. 3.2 pooled equations; Alg. 1 step 3) and
+// the channel-major copy of V that the attention kernel consumes.
+//
+// HBM-bound streaming reduction: one workgroup per (key block, batch*head, tensor), each
+// thread owns one 16-byte column chunk and walks the block's rows with all loads in
+// flight before the first add. Algorithmic traffic: 2 bytes read per input element, plus
+// 2 bytes written per V element for the channel-major copy.
+#include "rsa_common.hpp"
+
+namespace rsa {
+namespace {
+
+__device__ inline void accumulate8(float (&acc)[8], const uint4& v) {
+  const uint32_t w[4] = {v.x, v.y, v.z, v.w};
+#pragma unroll
+  for (int i = 0; i < 4; ++i) {
+    acc[2 * i] += bf16_bits_to_float(w[i] & 0xffffu);
+    acc[2 * i + 1] += bf16_bits_to_float(w[i] >> 16);
+  }
+}
+
+// Reduce the per-thread partial sums over the row groups and write the block mean
+// (fp32) and, optionally, its split into two bf16 terms hi + lo.
+template <int D, int RPP>
+__device__ inline void finish_mean(float (*red)[D], const float (&acc)[8], int r0, int cc, int count,
+                                   float* mean_out, uint16_t* hl_out) {
+#pragma unroll
+  for (int e = 0; e < 8; ++e) red[r0][cc * 8 + e] = acc[e];
+  __syncthreads();
+  const int tid = threadIdx.x;
+  if (tid < D) {
+    float s = 0.f;
+#pragma unroll
+    for (int r = 0; r < RPP; ++r) s += red[r][tid];
+    const float mean = s / (float)count;
+    mean_out[tid] = mean;
+    if (hl_out) {
+      const uint16_t hi = to_bf16_bits(mean);
+      hl_out[tid] = hi;
+      hl_out[D + tid] = to_bf16_bits(mean - bf16_bits_to_float(hi));
+    }
+  }
+}
+
+template <int D, int BLK>
+__global__ __launch_bounds__(256) void pool_qk_kernel(Dims dm, PoolArgs a) {
+  constexpr int CPR = D / 8;      // 16-byte chunks per row
+  constexpr int RPP = 256 / CPR;  // rows per pass
+  constexpr int NPASS = BLK / RPP;
+  __shared__ float red[RPP][D];
+  const int m = blockIdx.x, bh = blockIdx.y, which = blockIdx.z;
+  if (which == 0 && m >= dm.n) return;  // pooled queries exist for video blocks only
+  const int b = bh / dm.heads, h = bh % dm.heads;
+  const uint16_t* X = (which == 0 ? a.Q : a.K) + (int64_t)b * dm.sb + (int64_t)h * dm.sh;
+  const int64_t t0 = dm.block_start(m);
+  const int count = dm.block_count(m);
+  const int cc = threadIdx.x % CPR, r0 = threadIdx.x / CPR;
+
+  uint4 v[NPASS];
+#pragma unroll
+  for (int p = 0; p < NPASS; ++p) {
+    const int r = r0 + p * RPP;
+    v[p] = make_uint4(0, 0, 0, 0);
+    if (r < count) v[p] = *reinterpret_cast<const uint4*>(X + (t0 + r) * dm.st + cc * 8);
+  }
+  float acc[8] = {0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f};
+#pragma unroll
+  for (int p = 0; p < NPASS; ++p) accumulate8(acc, v[p]);
+
+  if (which == 0) {
+    const size_t row = (size_t)bh * dm.n + m;
+    finish_mean<D, RPP>(red, acc, r0, cc, count, a.Qp + row * D, a.QpHL ? a.QpHL + row * 2 * D : nullptr);
+  } else {
+    const size_t row = (size_t)bh * dm.m + m;
+    finish_mean<D, RPP>(red, acc, r0, cc, count, a.Kp + row * D, a.KpHL ? a.KpHL + row * 2 * D : nullptr);
+  }
+}
+
+// V: block mean plus the channel-major tile Vt[d][BLK]. Position 16c + 8h + 4g + e of a
+// channel row holds token 16c + 8g + 4h + e of the block (the two middle groups of four
+// swapped in every run of 16), which is the order in which one half-wave holds the
+// softmax probabilities after the S^T = K Q^T product; tokens past the block end are 0.
+template <int D, int BLK>
+__global__ __launch_bounds__(256) void pool_v_kernel(Dims dm, PoolArgs a) {
+  constexpr int CPR = D / 8;
+  constexpr int RPP = 256 / CPR;
+  constexpr int NPASS = BLK / RPP;
+  constexpr int TS = D / 2 + 1;  // tile row stride in 32-bit words (odd: spreads rows over banks)
+  __shared__ float red[RPP][D];
+  __shared__ uint32_t tile[BLK * TS];
+  const int m = blockIdx.x, bh = blockIdx.y;
+  const int b = bh / dm.heads, h = bh % dm.heads;
+  const uint16_t* X = a.V + (int64_t)b * dm.sb + (int64_t)h * dm.sh;
+  const int64_t t0 = dm.block_start(m);
+  const int count = dm.block_count(m);
+  const int cc = threadIdx.x % CPR, r0 = threadIdx.x / CPR;
+
+  uint4 v[NPASS];
+#pragma unroll
+  for (int p = 0; p < NPASS; ++p) {
+    const int r = r0 + p * RPP;
+    v[p] = make_uint4(0, 0, 0, 0);
+    if (r < count) v[p] = *reinterpret_cast<const uint4*>(X + (t0 + r) * dm.st + cc * 8);
+  }
+  float acc[8] = {0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f};
+#pragma unroll
+  for (int p = 0; p < NPASS; ++p) {
+    accumulate8(acc, v[p]);
+    uint32_t* dst = tile + (r0 + p * RPP) * TS + cc * 4;
+    dst[0] = v[p].x; dst[1] = v[p].y; dst[2] = v[p].z; dst[3] = v[p].w;
+  }
+  const size_t row = (size_t)bh * dm.m + m;
+  finish_mean<D, RPP>(red, acc, r0, cc, count, a.Vp + row * D, nullptr);  // contains a barrier
+
+  // Each thread emits, for one pair of adjacent channels, 8 consecutive positions.
+  uint16_t* out = a.Vt + row * (size_t)D * BLK;
+  constexpr int PCS = BLK / 8;                 // 16-byte chunks per channel row
+  constexpr int TASKS = (D / 2) * PCS;
+  for (int task = threadIdx.x; task < TASKS; task += 256) {
+    const int dpair = task / PCS, pc = task % PCS;
+    const int kv0 = 16 * (pc >> 1) + 4 * (pc & 1);
+    uint32_t w[8];
+#pragma unroll
+    for (int e = 0; e < 8; ++e) w[e] = tile[(kv0 + 8 * (e >> 2) + (e & 3)) * TS + dpair];
+    uint4 lo, hi;
+    lo.x = (w[0] & 0xffffu) | (w[1] << 16); hi.x = (w[0] >> 16) | (w[1] & 0xffff0000u);
+    lo.y = (w[2] & 0xffffu) | (w[3] << 16); hi.y = (w[2] >> 16) | (w[3] & 0xffff0000u);
+    lo.z = (w[4] & 0xffffu) | (w[5] << 16); hi.z = (w[4] >> 16) | (w[5] & 0xffff0000u);
+    lo.w = (w[6] & 0xffffu) | (w[7] << 16); hi.w = (w[6] >> 16) | (w[7] & 0xffff0000u);
+    *reinterpret_cast<uint4*>(out + (size_t)(2 * dpair) * BLK + pc * 8) = lo;
+    *reinterpret_cast<uint4*>(out + (size_t)(2 * dpair + 1) * BLK + pc * 8) = hi;
+  }
+}
+
+template <int D, int BLK>
+hipError_t launch_pool_t(const Dims& dm, const PoolArgs& a, hipStream_t s) {
+  const dim3 block(256);
+  hipLaunchKernelGGL((pool_qk_kernel<D, BLK>), dim3(dm.m, dm.batch * dm.heads, 2), block, 0, s, dm, a);
+  hipLaunchKernelGGL((pool_v_kernel<D, BLK>), dim3(dm.m, dm.batch * dm.heads, 1), block, 0, s, dm, a);
+  return hipGetLastError();
+}
+
+}  // namespace
+
+hipError_t launch_pool(const Dims& dm, const PoolArgs& a, hipStream_t s) {
+  if (dm.d == 128 && dm.blk == 128) return launch_pool_t<128, 128>(dm, a, s);
+  if (dm.d == 128 && dm.blk == 64) return launch_pool_t<128, 64>(dm, a, s);
+  if (dm.d == 64 && dm.blk == 128) return launch_pool_t<64, 128>(dm, a, s);
+  return launch_pool_t<64, 64>(dm, a, s);
+}
+
+}  // namespace rsa

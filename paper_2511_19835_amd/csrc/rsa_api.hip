@@ -1,0 +1,179 @@
+// C-ABI entry points of librsa.so: host-side validation, workspace carving, launches.
+#include <math.h>
+
+#include "rsa_common.hpp"
+
+namespace {
+
+using rsa::Dims;
+
+int make_dims(const rsa_shape* sh, Dims* out) {
+  if (!sh) return RSA_E_NULL;
+  if (sh->batch < 1 || sh->heads < 1 || sh->t_video < 1 || sh->t_text < 0) return RSA_E_SHAPE;
+  if (sh->head_dim != 64 && sh->head_dim != 128) return RSA_E_UNSUPPORTED;
+  if (sh->block != 64 && sh->block != 128) return RSA_E_UNSUPPORTED;
+  if (sh->stride_t < sh->head_dim || sh->stride_b < 1 || sh->stride_h < 1) return RSA_E_SHAPE;
+  if ((sh->stride_t % 8) || (sh->stride_b % 8) || (sh->stride_h % 8)) return RSA_E_SHAPE;
+  if (!(sh->scale >= 0.f) || !isfinite(sh->scale)) return RSA_E_RANGE;
+  Dims d;
+  d.batch = sh->batch;
+  d.heads = sh->heads;
+  d.d = sh->head_dim;
+  d.blk = sh->block;
+  d.tv = sh->t_video;
+  d.tt = sh->t_text;
+  d.t = d.tv + d.tt;
+  int64_t n = (d.tv + d.blk - 1) / d.blk;
+  int64_t mt = (d.tt + d.blk - 1) / d.blk;
+  if (n + mt > RSA_MAX_BLOCKS) return RSA_E_UNSUPPORTED;
+  if ((int64_t)d.batch * d.heads > 65535) return RSA_E_UNSUPPORTED;
+  d.n = (int)n;
+  d.mt = (int)mt;
+  d.m = (int)(n + mt);
+  d.w = (d.m + 31) / 32;
+  d.sb = sh->stride_b;
+  d.sh = sh->stride_h;
+  d.st = sh->stride_t;
+  d.scale = sh->scale > 0.f ? sh->scale : 1.0f / sqrtf((float)d.d);
+  *out = d;
+  return RSA_OK;
+}
+
+inline size_t align256(size_t x) { return (x + 255) & ~(size_t)255; }
+
+// Carving of the pooling workspace; every piece 256-byte aligned.
+struct PoolWs {
+  size_t qphl, kphl, da, dbt, total;
+};
+PoolWs pool_ws_layout(const Dims& d) {
+  size_t bh = (size_t)d.batch * d.heads;
+  PoolWs w;
+  size_t off = 0;
+  w.qphl = off; off += align256(bh * d.n * 2 * d.d * sizeof(uint16_t));
+  w.kphl = off; off += align256(bh * d.m * 2 * d.d * sizeof(uint16_t));
+  w.da = off;   off += align256(bh * (size_t)d.n * d.m * sizeof(float));
+  w.dbt = off;  off += align256(bh * (size_t)d.n * d.m * sizeof(float));
+  w.total = off;
+  return w;
+}
+
+}  // namespace
+
+extern "C" {
+
+int rsa_block_counts(const rsa_shape* shape, int64_t* n_video_blocks, int64_t* n_blocks,
+                     int64_t* mask_words) {
+  Dims d;
+  int rc = make_dims(shape, &d);
+  if (rc != RSA_OK) return rc;
+  if (n_video_blocks) *n_video_blocks = d.n;
+  if (n_blocks) *n_blocks = d.m;
+  if (mask_words) *mask_words = d.w;
+  return RSA_OK;
+}
+
+int rsa_workspace_bytes(const rsa_shape* shape, size_t* pool_ws_bytes, size_t* attn_ws_bytes) {
+  Dims d;
+  int rc = make_dims(shape, &d);
+  if (rc != RSA_OK) return rc;
+  if (pool_ws_bytes) *pool_ws_bytes = pool_ws_layout(d).total;
+  if (attn_ws_bytes) *attn_ws_bytes = 0;
+  return RSA_OK;
+}
+
+int rsa_pool(const rsa_shape* shape, const void* Q, const void* K, const void* V, float* Qp,
+             float* Kp, float* Vp, void* Vt, float* Spool, float* Apool, float* Lmass,
+             uint32_t* Mc_bits, int gapr_mode, void* ws, size_t ws_bytes, void* stream) {
+  Dims d;
+  int rc = make_dims(shape, &d);
+  if (rc != RSA_OK) return rc;
+  if (!Q || !K || !V || !Qp || !Kp || !Vp || !Vt || !Spool || !Apool || !Lmass || !Mc_bits)
+    return RSA_E_NULL;
+  if (gapr_mode < 0 || gapr_mode > 2) return RSA_E_RANGE;
+  PoolWs wl = pool_ws_layout(d);
+  if (!ws) return RSA_E_NULL;
+  if (ws_bytes < wl.total || ((uintptr_t)ws & 255)) return RSA_E_WORKSPACE;
+  hipStream_t s = (hipStream_t)stream;
+  char* wsb = (char*)ws;
+
+  rsa::PoolArgs pa;
+  pa.Q = (const uint16_t*)Q; pa.K = (const uint16_t*)K; pa.V = (const uint16_t*)V;
+  pa.Qp = Qp; pa.Kp = Kp; pa.Vp = Vp; pa.Vt = (uint16_t*)Vt;
+  pa.QpHL = (uint16_t*)(wsb + wl.qphl);
+  pa.KpHL = (uint16_t*)(wsb + wl.kphl);
+  if (rsa::launch_pool(d, pa, s) != hipSuccess) return RSA_E_LAUNCH;
+
+  rsa::ScoreArgs sa;
+  sa.K = (const uint16_t*)K; sa.Qp = Qp; sa.Kp = Kp;
+  sa.Spool = Spool; sa.Apool = Apool; sa.Lmass = Lmass;
+  if (rsa::launch_scores(d, sa, s) != hipSuccess) return RSA_E_LAUNCH;
+
+  rsa::GaprArgs ga;
+  ga.Q = (const uint16_t*)Q; ga.K = (const uint16_t*)K;
+  ga.QpHL = pa.QpHL; ga.KpHL = pa.KpHL; ga.Spool = Spool;
+  ga.DA = (float*)(wsb + wl.da); ga.DBt = (float*)(wsb + wl.dbt);
+  ga.Mc_bits = Mc_bits; ga.mode = gapr_mode;
+  if (rsa::launch_gapr(d, ga, s) != hipSuccess) return RSA_E_LAUNCH;
+  return RSA_OK;
+}
+
+int rsa_select_blocks(const rsa_shape* shape, const float* Lmass, const float* Apool,
+                      double sparsity, double p, const uint32_t* forced_bits,
+                      uint32_t* mask_bits, int32_t* block_idx, int32_t* count, float* R,
+                      void* stream) {
+  Dims d;
+  int rc = make_dims(shape, &d);
+  if (rc != RSA_OK) return rc;
+  if (!Lmass || !Apool || !mask_bits || !block_idx || !count || !R) return RSA_E_NULL;
+  if (!(sparsity >= 0.0 && sparsity <= 1.0) || !(p >= 0.0 && p <= 1.0)) return RSA_E_RANGE;
+  int64_t keep = (int64_t)d.m - (int64_t)floor(sparsity * (double)d.m + 1e-6);
+  if (keep < 1) keep = 1;
+  if (keep > d.m) keep = d.m;
+  rsa::SelectArgs sa;
+  sa.Lmass = Lmass; sa.Apool = Apool; sa.forced = forced_bits;
+  sa.mask_bits = mask_bits; sa.block_idx = block_idx; sa.count = count; sa.R = R;
+  sa.keep = (int)keep; sa.p = (float)p;
+  if (rsa::launch_select(d, sa, (hipStream_t)stream) != hipSuccess) return RSA_E_LAUNCH;
+  return RSA_OK;
+}
+
+int rsa_sparse_attn_rectified(const rsa_shape* shape, const void* Q, const void* K, const void* Vt,
+                              const int32_t* block_idx, const int32_t* count,
+                              const uint32_t* mask_bits, const float* R, const float* Apool,
+                              const uint32_t* Mc_bits, const float* Vp, int flags, void* O,
+                              float* lse, void* ws, size_t ws_bytes, void* stream) {
+  (void)ws; (void)ws_bytes;
+  Dims d;
+  int rc = make_dims(shape, &d);
+  if (rc != RSA_OK) return rc;
+  if (flags & ~(RSA_RECTIFY_CRITICAL | RSA_COMPENSATE | RSA_DENSE)) return RSA_E_RANGE;
+  if (!Q || !K || !Vt || !O) return RSA_E_NULL;
+  if (flags & RSA_DENSE) {
+    flags = RSA_DENSE;
+  } else {
+    if (!block_idx || !count) return RSA_E_NULL;
+    if ((flags & RSA_RECTIFY_CRITICAL) && !R) return RSA_E_NULL;
+    if ((flags & RSA_COMPENSATE) && (!mask_bits || !Apool || !Mc_bits || !Vp)) return RSA_E_NULL;
+  }
+  rsa::AttnArgs aa;
+  aa.Q = (const uint16_t*)Q; aa.K = (const uint16_t*)K; aa.Vt = (const uint16_t*)Vt;
+  aa.block_idx = block_idx; aa.count = count; aa.mask_bits = mask_bits; aa.Mc_bits = Mc_bits;
+  aa.R = R; aa.Apool = Apool; aa.Vp = Vp; aa.O = (uint16_t*)O; aa.lse = lse; aa.flags = flags;
+  if (rsa::launch_attn(d, aa, (hipStream_t)stream) != hipSuccess) return RSA_E_LAUNCH;
+  return RSA_OK;
+}
+
+const char* rsa_status_string(int status) {
+  switch (status) {
+    case RSA_OK: return "ok";
+    case RSA_E_NULL: return "a required pointer is NULL";
+    case RSA_E_SHAPE: return "invalid shape or strides";
+    case RSA_E_UNSUPPORTED: return "unsupported head_dim / block / block count";
+    case RSA_E_WORKSPACE: return "workspace too small or misaligned";
+    case RSA_E_RANGE: return "argument out of range";
+    case RSA_E_LAUNCH: return "HIP launch failed";
+    default: return "unknown status";
+  }
+}
+
+}  // extern "C"

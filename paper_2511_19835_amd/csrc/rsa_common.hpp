@@ -1,0 +1,96 @@
+// Shared declarations of the librsa.so translation units (gfx950 only).
+#pragma once
+
+#include <hip/hip_runtime.h>
+#include <stddef.h>
+#include <stdint.h>
+
+#include "rsa.h"
+
+namespace rsa {
+
+// Sizes derived from an rsa_shape; passed by value to every kernel.
+struct Dims {
+  int batch, heads, d, blk;
+  int64_t tv, tt, t;     // T_v, T_t, T
+  int n;                 // N: video blocks
+  int mt;                // text blocks
+  int m;                 // M = N + mt
+  int w;                 // mask words per row
+  int64_t sb, sh, st;    // element strides of Q/K/V/O
+  float scale;
+
+  __host__ __device__ inline int64_t block_start(int blk_idx) const {
+    return blk_idx < n ? (int64_t)blk_idx * blk : tv + (int64_t)(blk_idx - n) * blk;
+  }
+  __host__ __device__ inline int block_count(int blk_idx) const {
+    int64_t rem = blk_idx < n ? tv - (int64_t)blk_idx * blk : tt - (int64_t)(blk_idx - n) * blk;
+    return rem < blk ? (int)rem : blk;
+  }
+};
+
+typedef __bf16 bf16x8 __attribute__((ext_vector_type(8)));
+typedef __bf16 bf16x2 __attribute__((ext_vector_type(2)));
+typedef float floatx2 __attribute__((ext_vector_type(2)));
+typedef float floatx4 __attribute__((ext_vector_type(4)));
+typedef float floatx16 __attribute__((ext_vector_type(16)));
+
+__device__ inline float bf16_bits_to_float(uint32_t bits16) {
+  return __builtin_bit_cast(float, bits16 << 16);
+}
+// Round-to-nearest-even pair conversion (v_cvt_pk_bf16_f32): low half = a, high half = b.
+__device__ inline uint32_t pack_bf16x2(float a, float b) {
+  floatx2 f = {a, b};
+  return __builtin_bit_cast(uint32_t, __builtin_convertvector(f, bf16x2));
+}
+__device__ inline uint16_t to_bf16_bits(float a) { return (uint16_t)(pack_bf16x2(a, 0.f) & 0xffffu); }
+
+// ---- launchers (one per translation unit) -------------------------------------------
+struct PoolArgs {
+  const uint16_t *Q, *K, *V;
+  float *Qp, *Kp, *Vp;
+  uint16_t* Vt;
+  uint16_t *QpHL, *KpHL;   // optional [.., 2, d] bf16 hi/lo split of the pooled vectors
+};
+hipError_t launch_pool(const Dims& dm, const PoolArgs& a, hipStream_t s);
+
+struct ScoreArgs {
+  const uint16_t* K;
+  const float *Qp, *Kp;
+  float *Spool, *Apool, *Lmass;
+};
+hipError_t launch_scores(const Dims& dm, const ScoreArgs& a, hipStream_t s);
+
+struct GaprArgs {
+  const uint16_t *Q, *K;
+  const uint16_t *QpHL, *KpHL;
+  const float* Spool;
+  float *DA, *DBt;         // [b][h][N][M], [b][h][M][N]
+  uint32_t* Mc_bits;
+  int mode;
+};
+hipError_t launch_gapr(const Dims& dm, const GaprArgs& a, hipStream_t s);
+
+struct SelectArgs {
+  const float *Lmass, *Apool;
+  const uint32_t* forced;
+  uint32_t* mask_bits;
+  int32_t *block_idx, *count;
+  float* R;
+  int keep;
+  float p;
+};
+hipError_t launch_select(const Dims& dm, const SelectArgs& a, hipStream_t s);
+
+struct AttnArgs {
+  const uint16_t *Q, *K, *Vt;
+  const int32_t *block_idx, *count;
+  const uint32_t *mask_bits, *Mc_bits;
+  const float *R, *Apool, *Vp;
+  uint16_t* O;
+  float* lse;
+  int flags;
+};
+hipError_t launch_attn(const Dims& dm, const AttnArgs& a, hipStream_t s);
+
+}  // namespace rsa

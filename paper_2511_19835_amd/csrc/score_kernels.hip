@@ -1,0 +1,199 @@
+// Implicit full attention from pooled query-key interactions (paper Sec. 3.2, Sec. 4.1;
+// Alg. 1 steps 5-7). Everything stays fp32: the selection that follows compares these
+// values and is checked against an fp64 reference inside a 1e-4 band.
+//
+//   pooled_scores_kernel   Spool[n][m] = scale * q^pool_n . k^pool_m       (N x M x d, tiny)
+//   text_mass_kernel       Lmass[n][N+i] = log sum_{t in text block i} exp(scale * q^pool_n . k_t)
+//   ipar_softmax_kernel    Lmass[n][m<N] = Spool + ln c_m ; Apool = row-softmax(Lmass)
+//
+// softmax(Lmass) is the paper's reallocation written in log space: the mixed softmax
+// over [pooled video keys ; text tokens] gives weights proportional to exp(score); a video
+// block is then multiplied by its token count (exp(s + ln c)), text tokens are summed per
+// block (exp(logsumexp)), and everything is divided by the row total.
+#include "rsa_common.hpp"
+
+namespace rsa {
+namespace {
+
+__device__ inline float wave_max(float v) {
+#pragma unroll
+  for (int o = 32; o > 0; o >>= 1) v = fmaxf(v, __shfl_xor(v, o));
+  return v;
+}
+__device__ inline float wave_sum(float v) {
+#pragma unroll
+  for (int o = 32; o > 0; o >>= 1) v += __shfl_xor(v, o);
+  return v;
+}
+
+// 64 x 64 output tile per workgroup, 4 x 4 per thread, k in chunks of 32 through LDS.
+template <int D>
+__global__ __launch_bounds__(256) void pooled_scores_kernel(Dims dm, ScoreArgs a) {
+  constexpr int KC = 32;
+  __shared__ float qs[64][KC + 1];
+  __shared__ float ks[64][KC + 1];
+  const int bh = blockIdx.z;
+  const int n0 = blockIdx.y * 64, m0 = blockIdx.x * 64;
+  const float* Qp = a.Qp + (size_t)bh * dm.n * D;
+  const float* Kp = a.Kp + (size_t)bh * dm.m * D;
+  const int tx = threadIdx.x % 16, ty = threadIdx.x / 16;
+  float acc[4][4];
+#pragma unroll
+  for (int i = 0; i < 4; ++i)
+#pragma unroll
+    for (int j = 0; j < 4; ++j) acc[i][j] = 0.f;
+
+  for (int k0 = 0; k0 < D; k0 += KC) {
+    // 64 rows x 32 floats per operand = 2048 floats, 8 per thread
+#pragma unroll
+    for (int i = 0; i < 8; ++i) {
+      const int idx = threadIdx.x + i * 256;
+      const int r = idx / KC, c = idx % KC;
+      qs[r][c] = (n0 + r < dm.n) ? Qp[(size_t)(n0 + r) * D + k0 + c] : 0.f;
+      ks[r][c] = (m0 + r < dm.m) ? Kp[(size_t)(m0 + r) * D + k0 + c] : 0.f;
+    }
+    __syncthreads();
+#pragma unroll
+    for (int kk = 0; kk < KC; ++kk) {
+      float qa[4], kb[4];
+#pragma unroll
+      for (int i = 0; i < 4; ++i) qa[i] = qs[ty * 4 + i][kk];
+#pragma unroll
+      for (int j = 0; j < 4; ++j) kb[j] = ks[tx * 4 + j][kk];
+#pragma unroll
+      for (int i = 0; i < 4; ++i)
+#pragma unroll
+        for (int j = 0; j < 4; ++j) acc[i][j] = fmaf(qa[i], kb[j], acc[i][j]);
+    }
+    __syncthreads();
+  }
+  float* S = a.Spool + (size_t)bh * dm.n * dm.m;
+#pragma unroll
+  for (int i = 0; i < 4; ++i) {
+    const int n = n0 + ty * 4 + i;
+    if (n >= dm.n) continue;
+#pragma unroll
+    for (int j = 0; j < 4; ++j) {
+      const int m = m0 + tx * 4 + j;
+      if (m < dm.m) S[(size_t)n * dm.m + m] = acc[i][j] * dm.scale;
+    }
+  }
+}
+
+// Eight pooled queries per workgroup against the individual text keys, 256 tokens at a
+// time (a multiple of the block size), then one log-sum-exp per (query, text block).
+template <int D, int BLK>
+__global__ __launch_bounds__(256) void text_mass_kernel(Dims dm, ScoreArgs a) {
+  constexpr int NQ = 8;
+  __shared__ float qs[NQ][D];
+  __shared__ float u[NQ][256];
+  const int bh = blockIdx.y;
+  const int b = bh / dm.heads, h = bh % dm.heads;
+  const int n0 = blockIdx.x * NQ;
+  const float* Qp = a.Qp + (size_t)bh * dm.n * D;
+  for (int idx = threadIdx.x; idx < NQ * D; idx += 256) {
+    const int r = idx / D, c = idx % D;
+    qs[r][c] = (n0 + r < dm.n) ? Qp[(size_t)(n0 + r) * D + c] : 0.f;
+  }
+  __syncthreads();
+  const uint16_t* Kt = a.K + (int64_t)b * dm.sb + (int64_t)h * dm.sh + dm.tv * dm.st;
+  float* L = a.Lmass + (size_t)bh * dm.n * dm.m;
+  const int wave = threadIdx.x / 64, lane = threadIdx.x % 64;
+
+  for (int64_t c0 = 0; c0 < dm.tt; c0 += 256) {
+    const int64_t tok = c0 + threadIdx.x;
+    float acc[NQ];
+#pragma unroll
+    for (int r = 0; r < NQ; ++r) acc[r] = 0.f;
+    if (tok < dm.tt) {
+      const uint4* row = reinterpret_cast<const uint4*>(Kt + tok * dm.st);
+#pragma unroll 4
+      for (int cc = 0; cc < D / 8; ++cc) {
+        const uint4 v = row[cc];
+        const uint32_t w[4] = {v.x, v.y, v.z, v.w};
+#pragma unroll
+        for (int i = 0; i < 4; ++i) {
+          const float k0 = bf16_bits_to_float(w[i] & 0xffffu), k1 = bf16_bits_to_float(w[i] >> 16);
+#pragma unroll
+          for (int r = 0; r < NQ; ++r) {
+            acc[r] = fmaf(qs[r][cc * 8 + 2 * i], k0, acc[r]);
+            acc[r] = fmaf(qs[r][cc * 8 + 2 * i + 1], k1, acc[r]);
+          }
+        }
+      }
+    }
+#pragma unroll
+    for (int r = 0; r < NQ; ++r) u[r][threadIdx.x] = acc[r] * dm.scale;
+    __syncthreads();
+    // tasks: (query r, block j of this chunk); one wave per task
+    constexpr int BPC = 256 / BLK;
+    for (int task = wave; task < NQ * BPC; task += 4) {
+      const int r = task / BPC, j = task % BPC;
+      const int64_t first = c0 + (int64_t)j * BLK;
+      if (first >= dm.tt || n0 + r >= dm.n) continue;
+      const int cnt = (int)((dm.tt - first) < BLK ? (dm.tt - first) : BLK);
+      float mx = -INFINITY;
+      for (int i = lane; i < cnt; i += 64) mx = fmaxf(mx, u[r][j * BLK + i]);
+      mx = wave_max(mx);
+      float sum = 0.f;
+      for (int i = lane; i < cnt; i += 64) sum += expf(u[r][j * BLK + i] - mx);
+      sum = wave_sum(sum);
+      if (lane == 0) L[(size_t)(n0 + r) * dm.m + dm.n + (int)(first / BLK)] = mx + logf(sum);
+    }
+    __syncthreads();
+  }
+}
+
+__global__ __launch_bounds__(256) void ipar_softmax_kernel(Dims dm, ScoreArgs a) {
+  __shared__ float red[8];
+  const int n = blockIdx.x, bh = blockIdx.y;
+  const size_t row = ((size_t)bh * dm.n + n) * dm.m;
+  const float* S = a.Spool + row;
+  float* L = a.Lmass + row;
+  float* A = a.Apool + row;
+  const int wave = threadIdx.x / 64, lane = threadIdx.x % 64;
+  float mx = -INFINITY;
+  for (int m = threadIdx.x; m < dm.m; m += 256) {
+    float l;
+    if (m < dm.n) {
+      l = S[m] + logf((float)dm.block_count(m));
+      L[m] = l;
+    } else {
+      l = L[m];
+    }
+    mx = fmaxf(mx, l);
+  }
+  mx = wave_max(mx);
+  if (lane == 0) red[wave] = mx;
+  __syncthreads();
+  mx = fmaxf(fmaxf(red[0], red[1]), fmaxf(red[2], red[3]));
+  float sum = 0.f;
+  for (int m = threadIdx.x; m < dm.m; m += 256) sum += expf(L[m] - mx);
+  sum = wave_sum(sum);
+  if (lane == 0) red[4 + wave] = sum;
+  __syncthreads();
+  sum = (red[4] + red[5]) + (red[6] + red[7]);
+  const float inv = 1.0f / sum;
+  for (int m = threadIdx.x; m < dm.m; m += 256) A[m] = expf(L[m] - mx) * inv;
+}
+
+template <int D, int BLK>
+hipError_t launch_scores_t(const Dims& dm, const ScoreArgs& a, hipStream_t s) {
+  const int bh = dm.batch * dm.heads;
+  hipLaunchKernelGGL((pooled_scores_kernel<D>), dim3((dm.m + 63) / 64, (dm.n + 63) / 64, bh), dim3(256), 0, s, dm, a);
+  if (dm.tt > 0)
+    hipLaunchKernelGGL((text_mass_kernel<D, BLK>), dim3((dm.n + 7) / 8, bh), dim3(256), 0, s, dm, a);
+  hipLaunchKernelGGL(ipar_softmax_kernel, dim3(dm.n, bh), dim3(256), 0, s, dm, a);
+  return hipGetLastError();
+}
+
+}  // namespace
+
+hipError_t launch_scores(const Dims& dm, const ScoreArgs& a, hipStream_t s) {
+  if (dm.d == 128 && dm.blk == 128) return launch_scores_t<128, 128>(dm, a, s);
+  if (dm.d == 128 && dm.blk == 64) return launch_scores_t<128, 64>(dm, a, s);
+  if (dm.d == 64 && dm.blk == 128) return launch_scores_t<64, 128>(dm, a, s);
+  return launch_scores_t<64, 64>(dm, a, s);
+}
+
+}  // namespace rsa

@@ -1,0 +1,140 @@
+// Sparse-mask generation and rectification factor (paper Alg. 1 steps 13-14 and 19;
+// Sec. 4.1 for R_n, Sec. 4.3 and the appendix "Implementations" for top-k and p).
+//
+// One wavefront per video query block. The row's M log-masses become order-preserving
+// 32-bit keys held in LDS, lane l owning blocks l, l+64, ...; the k-th largest key is found
+// by a 32-step bitwise search whose counts are wave ballots, so the selection is exact
+// integer work (ties: lower block index first). The optional weight threshold p extends
+// the kept prefix, in the same descending order, until the kept A^pool exceeds p.
+// Outputs: mask bits, ascending block list, count, and R_n = sum of kept A^pool.
+#include "rsa_common.hpp"
+
+namespace rsa {
+namespace {
+
+__device__ inline uint32_t orderable_key(float x) {
+  const uint32_t u = __builtin_bit_cast(uint32_t, x);
+  return (u & 0x80000000u) ? ~u : (u | 0x80000000u);
+}
+__device__ inline int lanes_below(unsigned long long mask) {
+  return __builtin_amdgcn_mbcnt_hi((uint32_t)(mask >> 32), __builtin_amdgcn_mbcnt_lo((uint32_t)mask, 0));
+}
+__device__ inline float wave_sum(float v) {
+#pragma unroll
+  for (int o = 32; o > 0; o >>= 1) v += __shfl_xor(v, o);
+  return v;
+}
+__device__ inline float wave_inclusive_scan(float v, int lane) {
+#pragma unroll
+  for (int o = 1; o < 64; o <<= 1) {
+    const float up = __shfl_up(v, o);
+    if (lane >= o) v += up;
+  }
+  return v;
+}
+
+__global__ __launch_bounds__(64) void select_kernel(Dims dm, SelectArgs a) {
+  extern __shared__ uint32_t smem[];
+  const int lane = threadIdx.x;
+  const int n = blockIdx.x, bh = blockIdx.y;
+  const int M = dm.m;
+  const int slots = (M + 63) / 64;
+  uint32_t* keys = smem;
+  float* vals = reinterpret_cast<float*>(smem + slots * 64);
+  const size_t row = (size_t)bh * dm.n + n;
+  const float* L = a.Lmass + row * M;
+  const float* A = a.Apool + row * M;
+
+  for (int s = 0; s < slots; ++s) {
+    const int m = s * 64 + lane;
+    keys[m] = (m < M) ? orderable_key(L[m]) : 0u;   // 0 sorts below every real key
+    vals[m] = (m < M) ? A[m] : 0.f;
+  }
+  // every lane only ever reads back the entries it wrote: no barrier needed
+
+  // k-th largest key
+  uint32_t tau = 0;
+  for (int bit = 31; bit >= 0; --bit) {
+    const uint32_t cand = tau | (1u << bit);
+    int cnt = 0;
+    for (int s = 0; s < slots; ++s) cnt += __popcll(__ballot(keys[s * 64 + lane] >= cand));
+    if (cnt >= a.keep) tau = cand;
+  }
+  int n_gt = 0;
+  for (int s = 0; s < slots; ++s) n_gt += __popcll(__ballot(keys[s * 64 + lane] > tau));
+  int ties = a.keep - n_gt;       // how many blocks equal to tau are kept (index order)
+  int kept_target = a.keep;
+
+  if (a.p > 0.f) {
+    // largest threshold whose kept weight exceeds p
+    uint32_t tau_p = 0;
+    for (int bit = 31; bit >= 0; --bit) {
+      const uint32_t cand = tau_p | (1u << bit);
+      float part = 0.f;
+      for (int s = 0; s < slots; ++s) part += (keys[s * 64 + lane] >= cand) ? vals[s * 64 + lane] : 0.f;
+      if (wave_sum(part) > a.p) tau_p = cand;
+    }
+    float part = 0.f;
+    int n_gt_p = 0;
+    for (int s = 0; s < slots; ++s) {
+      const bool gt = keys[s * 64 + lane] > tau_p;
+      part += gt ? vals[s * 64 + lane] : 0.f;
+      n_gt_p += __popcll(__ballot(gt));
+    }
+    float run = wave_sum(part);    // weight strictly above tau_p: not yet above p
+    int ties_p = 0;
+    if (tau_p != 0) {
+      for (int s = 0; s < slots; ++s) {
+        const bool tie = keys[s * 64 + lane] == tau_p;
+        const float tv = tie ? vals[s * 64 + lane] : 0.f;
+        const float incl = wave_inclusive_scan(tv, lane);
+        ties_p += __popcll(__ballot(tie && (run + (incl - tv) <= a.p)));
+        run += __shfl(incl, 63);
+      }
+    }
+    if (n_gt_p + ties_p > kept_target) {
+      kept_target = n_gt_p + ties_p;
+      tau = tau_p;
+      ties = ties_p;
+    }
+  }
+
+  const uint32_t* forced = a.forced ? a.forced + row * dm.w : nullptr;
+  uint32_t* mbits = a.mask_bits + row * dm.w;
+  int32_t* list = a.block_idx + row * M;
+  int list_base = 0, tie_base = 0;
+  float rpart = 0.f;
+  for (int s = 0; s < slots; ++s) {
+    const int m = s * 64 + lane;
+    const uint32_t key = keys[m];
+    const bool tie = key == tau && m < M;
+    const unsigned long long tie_mask = __ballot(tie);
+    bool kept = (key > tau) || (tie && (tie_base + lanes_below(tie_mask) < ties));
+    tie_base += __popcll(tie_mask);
+    const int word = 2 * s + (lane >> 5);
+    if (forced && m < M) kept = kept || ((forced[word] >> (lane & 31)) & 1u);
+    const unsigned long long kept_mask = __ballot(kept);
+    if ((lane & 31) == 0 && word < dm.w) mbits[word] = (uint32_t)(kept_mask >> (lane & 32));
+    if (kept) {
+      list[list_base + lanes_below(kept_mask)] = m;
+      rpart += vals[m];
+    }
+    list_base += __popcll(kept_mask);
+  }
+  const float r = wave_sum(rpart);
+  if (lane == 0) {
+    a.count[row] = list_base;
+    a.R[row] = r;
+  }
+}
+
+}  // namespace
+
+hipError_t launch_select(const Dims& dm, const SelectArgs& a, hipStream_t s) {
+  const int slots = (dm.m + 63) / 64;
+  const size_t lds = (size_t)slots * 64 * 2 * sizeof(uint32_t);
+  hipLaunchKernelGGL(select_kernel, dim3(dm.n, dm.batch * dm.heads), dim3(64), lds, s, dm, a);
+  return hipGetLastError();
+}
+
+}  // namespace rsa

@@ -1,0 +1,77 @@
+"""Host-side plumbing around the binding: upload bit patterns, run a layer, download.
+
+No arithmetic of the method happens here; it exists so tests, the smoke check and the
+benchmark drive the C-ABI the same way.
+"""
+from __future__ import annotations
+
+from typing import Optional
+
+import numpy as np
+import torch
+
+from . import binding as rb
+
+
+def bits_to_device(bits: np.ndarray, device="cuda:0", layout: str = "bhtd") -> torch.Tensor:
+    """uint16 bf16 bit patterns [B,H,T,d] -> bf16 device tensor viewed as [B,H,T,d].
+
+    layout "bhtd": contiguous as given; "bthd": memory order [B,T,H,d] (heads interleaved
+    per token), returned as a permuted view so the strides differ."""
+    t = torch.from_numpy(np.ascontiguousarray(bits).view(np.int16)).to(device).view(torch.bfloat16)
+    if layout == "bhtd":
+        return t
+    if layout == "bthd":
+        return t.permute(0, 2, 1, 3).contiguous().permute(0, 2, 1, 3)
+    raise ValueError(layout)
+
+
+def device_to_bits(t: torch.Tensor) -> np.ndarray:
+    return t.contiguous().view(torch.int16).cpu().numpy().view(np.uint16)
+
+
+def unpack_bits(words: np.ndarray, n_bits: int) -> np.ndarray:
+    """[..., W] int32/uint32 words -> [..., n_bits] bool (bit m%32 of word m/32)."""
+    w = np.ascontiguousarray(words).view(np.uint32)
+    bits = (w[..., :, None] >> np.arange(32, dtype=np.uint32)) & np.uint32(1)
+    return bits.reshape(*w.shape[:-1], -1)[..., :n_bits].astype(bool)
+
+
+def pack_bits(mask: np.ndarray) -> np.ndarray:
+    """[..., M] bool -> [..., ceil(M/32)] int32 words."""
+    M = mask.shape[-1]
+    W = (M + 31) // 32
+    padded = np.zeros(mask.shape[:-1] + (W * 32,), dtype=np.uint32)
+    padded[..., :M] = mask
+    words = (padded.reshape(*mask.shape[:-1], W, 32) << np.arange(32, dtype=np.uint32)).sum(axis=-1, dtype=np.uint64)
+    return words.astype(np.uint32).view(np.int32)
+
+
+def run_layer(Q_bits: np.ndarray, K_bits: np.ndarray, V_bits: np.ndarray, t_video: int, t_text: int,
+              block: int, sparsity: float, p: float = 0.0, gapr_mode: int = 1,
+              forced: Optional[np.ndarray] = None, flags: int = rb.RSA_RECTIFY_CRITICAL | rb.RSA_COMPENSATE,
+              scale: float = 0.0, layout: str = "bhtd", device="cuda:0", want_lse: bool = True) -> dict:
+    """Run the three entry points on the GPU and bring every buffer back as numpy."""
+    Q = bits_to_device(Q_bits, device, layout)
+    K = bits_to_device(K_bits, device, layout)
+    V = bits_to_device(V_bits, device, layout)
+    O = torch.empty_like(Q)
+    buf = rb.allocate(Q, t_video, t_text, block, scale)
+    forced_dev = None
+    if forced is not None:
+        forced_dev = torch.from_numpy(pack_bits(np.asarray(forced, dtype=bool))).to(device)
+    B, H, T, _ = Q.shape
+    lse = torch.empty(B, H, T, dtype=torch.float32, device=device) if want_lse else None
+    rb.rectified_sparse_attention(Q, K, V, O, buf, sparsity, p, gapr_mode, forced_dev, flags, lse)
+    torch.cuda.synchronize()
+    out = dict(
+        N=buf.N, M=buf.M, W=buf.W,
+        Qp=buf.Qp.cpu().numpy(), Kp=buf.Kp.cpu().numpy(), Vp=buf.Vp.cpu().numpy(),
+        Vt_bits=device_to_bits(buf.Vt),
+        Spool=buf.Spool.cpu().numpy(), Apool=buf.Apool.cpu().numpy(), Lmass=buf.Lmass.cpu().numpy(),
+        Mc=unpack_bits(buf.Mc_bits.cpu().numpy(), buf.M), mask=unpack_bits(buf.mask_bits.cpu().numpy(), buf.M),
+        Mc_words=buf.Mc_bits.cpu().numpy(), mask_words=buf.mask_bits.cpu().numpy(),
+        block_idx=buf.block_idx.cpu().numpy(), count=buf.count.cpu().numpy(), R=buf.R.cpu().numpy(),
+        O_bits=device_to_bits(O), lse=lse.cpu().numpy() if lse is not None else None,
+    )
+    return out

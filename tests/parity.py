@@ -1,0 +1,125 @@
+"""Element-by-element comparison of the HIP path's buffers with the CPU oracle.
+
+Tolerances (derivation in DESIGN.md, "Tolerances"):
+  * block masks: bit-exact, except blocks whose log-mass lies within 1e-4 of the row's
+    selection threshold (the k-th largest log-mass); the kept count must still match;
+  * compensation mask: bit-exact, except blocks where gain and error differ by less than
+    1e-3 relative;
+  * pooled tensors / scores / A^pool / R: fp32-vs-fp64 rounding;
+  * outputs: max-abs <= 2e-2 and relative L2 <= 5e-3 (bf16 inputs, fp32 accumulation).
+Where a near-threshold block legitimately differs, the oracle output of that row is
+recomputed with the mask the GPU chose, so what is compared stays unique.
+"""
+from __future__ import annotations
+
+from typing import Iterable, Optional
+
+import numpy as np
+
+from oracle import rsa_oracle as ro
+
+MASK_BAND = 1e-4
+GATE_BAND = 1e-3
+OUT_MAX_ABS = 2e-2
+OUT_REL_L2 = 5e-3
+
+
+def bf16_bits_to_f64(bits):
+    return ro.bf16_bits_to_f64(bits)
+
+
+def oracle_head(Qb, Kb, Vb, t_video, t_text, block, sparsity, **kw):
+    return ro.rectified_layer_head(ro.bf16_bits_to_f64(Qb), ro.bf16_bits_to_f64(Kb), ro.bf16_bits_to_f64(Vb),
+                                   t_video, t_text, block, sparsity, **kw)
+
+
+def compare_head(gpu: dict, b: int, h: int, ref: dict, Qb, Kb, Vb, *, p: float = 0.0,
+                 forced: Optional[np.ndarray] = None, rectify: bool = True, compensate: bool = True,
+                 query_blocks: Optional[Iterable[int]] = None, check_vt: bool = True) -> dict:
+    """Assert parity of one (batch, head); returns a few statistics. ``ref`` is the oracle's
+    dict for the same inputs (its O may be restricted to ``query_blocks``)."""
+    part = ref["part"]
+    N, M = part.n_video, part.n_blocks
+    stats = {}
+
+    # ---- pooled vectors, scores, implicit attention --------------------------------------
+    np.testing.assert_allclose(gpu["Qp"][b, h], ref["Qp"][:N], rtol=2e-6, atol=2e-6)
+    np.testing.assert_allclose(gpu["Kp"][b, h], ref["Kp"], rtol=2e-6, atol=2e-6)
+    np.testing.assert_allclose(gpu["Vp"][b, h], ref["Vp"], rtol=2e-6, atol=2e-6)
+    np.testing.assert_allclose(gpu["Spool"][b, h], ref["S_pool"], rtol=1e-5, atol=2e-5)
+    np.testing.assert_allclose(gpu["Apool"][b, h], ref["A_pool"], rtol=2e-4, atol=1e-9)
+    np.testing.assert_allclose(gpu["Apool"][b, h].sum(axis=1), 1.0, atol=1e-5)
+    logA = np.log(np.maximum(ref["A_pool"], 1e-300))
+    lm = gpu["Lmass"][b, h].astype(np.float64)
+    lm_norm = lm - (np.log(np.exp(lm - lm.max(axis=1, keepdims=True)).sum(axis=1, keepdims=True))
+                    + lm.max(axis=1, keepdims=True))
+    np.testing.assert_allclose(lm_norm, logA, atol=3e-5)
+
+    # ---- channel-major V tiles: exact copies ------------------------------------------------
+    if check_vt:
+        vt = gpu["Vt_bits"][b, h]                       # [M, d, B]
+        B = part.block
+        pos = np.arange(B)
+        tok_of_pos = 16 * (pos // 16) + 8 * ((pos % 8) // 4) + 4 * ((pos % 16) // 8) + pos % 4
+        for m in (0, N - 1, M - 1, M // 2):
+            cnt = int(part.counts[m])
+            want = np.zeros((B, Vb.shape[1]), dtype=np.uint16)
+            want[:cnt] = Vb[part.tokens(m)]
+            np.testing.assert_array_equal(vt[m], want[tok_of_pos].T)
+
+    # ---- sparse mask --------------------------------------------------------------------------
+    gmask = gpu["mask"][b, h]
+    rmask = ref["mask"]
+    diff_rows = np.nonzero((gmask != rmask).any(axis=1))[0]
+    if diff_rows.size:
+        k = int(rmask[0].sum()) if (p == 0.0 and forced is None) else None
+        for n in diff_rows:
+            d = np.nonzero(gmask[n] != rmask[n])[0]
+            kept_sorted = np.sort(logA[n][rmask[n] & ~(forced[n] if forced is not None else False)])
+            tau = kept_sorted[0]
+            assert np.all(np.abs(logA[n][d] - tau) <= MASK_BAND), \
+                f"mask differs outside the threshold band at row {n}: blocks {d}, dist {np.abs(logA[n][d] - tau)}"
+            if k is not None:
+                assert gmask[n].sum() == k
+    stats["mask_rows_in_band"] = int(diff_rows.size)
+    cnt = gpu["count"][b, h]
+    np.testing.assert_array_equal(cnt, gmask.sum(axis=1))
+    for n in (0, N // 2, N - 1):
+        np.testing.assert_array_equal(gpu["block_idx"][b, h, n, :cnt[n]], np.nonzero(gmask[n])[0])
+
+    # ---- compensation mask -------------------------------------------------------------------
+    gmc = gpu["Mc"][b, h]
+    mcdiff = gmc != ref["Mc"]
+    if mcdiff.any():
+        G, E = ref["G"], ref["E"]
+        rel = np.abs(G - E) / np.maximum(np.maximum(G, E), 1e-300)
+        assert np.all(rel[mcdiff] <= GATE_BAND), f"M_c differs outside the band: {rel[mcdiff].max()}"
+    stats["mc_in_band"] = int(mcdiff.sum())
+
+    # ---- factor -------------------------------------------------------------------------------
+    R_ref = (ref["A_pool"] * gmask).sum(axis=1)           # with the mask the GPU chose
+    np.testing.assert_allclose(gpu["R"][b, h], R_ref, rtol=2e-4, atol=1e-7)
+
+    # ---- outputs ------------------------------------------------------------------------------
+    O_gpu = ro.bf16_bits_to_f64(gpu["O_bits"][b, h])
+    O_ref = ref["O"].copy()
+    blocks = list(range(M)) if query_blocks is None else [int(x) for x in query_blocks]
+    redo = [n for n in blocks if n < N and ((gmask[n] != rmask[n]).any() or (mcdiff[n] & ~gmask[n]).any())]
+    if redo:
+        Q, K, V = (ro.bf16_bits_to_f64(x) for x in (Qb, Kb, Vb))
+        for n in redo:
+            o = ro.sparse_attention_block(Q, K, V, gmask[n], n, part, ref["scale"])
+            if rectify:
+                o = o * R_ref[n]
+            if compensate:
+                o = o + ((ref["A_pool"][n] * (~gmask[n] & gmc[n])) @ ref["Vp"])[None, :]
+            O_ref[part.tokens(n)] = o
+    rows = np.concatenate([np.arange(part.starts[n], part.starts[n] + part.counts[n]) for n in blocks])
+    err = O_gpu[rows] - O_ref[rows]
+    assert np.isfinite(O_gpu[rows]).all()
+    max_abs = float(np.abs(err).max())
+    rel_l2 = float(np.linalg.norm(err) / max(np.linalg.norm(O_ref[rows]), 1e-300))
+    assert max_abs <= OUT_MAX_ABS, f"max-abs {max_abs}"
+    assert rel_l2 <= OUT_REL_L2, f"rel-L2 {rel_l2}"
+    stats.update(max_abs=max_abs, rel_l2=rel_l2, rows=int(rows.size), redo=len(redo))
+    return stats

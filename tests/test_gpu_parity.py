@@ -1,0 +1,212 @@
+"""GPU parity: the HIP path behind the C-ABI against the CPU oracle, element by element,
+on the same seeded inputs. Needs an MI355X: run with ``-m gpu``."""
+import numpy as np
+import pytest
+
+from paper_2511_19835_amd import synth
+from paper_2511_19835_amd.synth import LayerConfig
+
+pytestmark = pytest.mark.gpu
+
+
+@pytest.fixture(scope="module")
+def gpu():
+    import torch
+    if not torch.cuda.is_available():
+        pytest.fail("no GPU visible: these tests must run on the MI355X box")
+    from paper_2511_19835_amd import binding, harness
+    binding.load_library()          # fails loudly if librsa.so is missing
+    return harness
+
+
+def _run_and_compare(harness, cfg, seed=0, heads=None, layout="bhtd", **kw):
+    import parity
+    Qb, Kb, Vb = synth.make_inputs(cfg, seed, heads)
+    sparsity = kw.pop("sparsity", cfg.sparsity)
+    p = kw.get("p", 0.0)
+    gapr_mode = kw.get("gapr_mode", 1)
+    forced = kw.get("forced", None)
+    flags = kw.get("flags", 3)
+    out = harness.run_layer(Qb, Kb, Vb, cfg.t_video, cfg.t_text, cfg.block, sparsity, p=p, gapr_mode=gapr_mode,
+                            forced=forced, flags=flags, layout=layout)
+    stats = []
+    for b in range(Qb.shape[0]):
+        for h in range(Qb.shape[1]):
+            ref = parity.oracle_head(Qb[b, h], Kb[b, h], Vb[b, h], cfg.t_video, cfg.t_text, cfg.block, sparsity,
+                                     p=p, gapr_mode=gapr_mode,
+                                     forced=None if forced is None else forced[b, h],
+                                     rectify=bool(flags & 1), compensate=bool(flags & 2))
+            st = parity.compare_head(out, b, h, ref, Qb[b, h], Kb[b, h], Vb[b, h], p=p,
+                                     forced=None if forced is None else forced[b, h],
+                                     rectify=bool(flags & 1), compensate=bool(flags & 2))
+            stats.append(st)
+            print(f"  [{cfg.name} b{b} h{h}] {st}", flush=True)
+    return out, stats, (Qb, Kb, Vb)
+
+
+def test_tiny_config_full_parity(gpu):
+    """BASELINE config 0: 2 heads, d 64, 1024 video + 64 text tokens, block 64, 75 % sparsity."""
+    import parity
+    from oracle import rsa_oracle as ro
+    cfg = synth.CONFIGS["tiny"]
+    out, stats, (Qb, Kb, Vb) = _run_and_compare(gpu, cfg)
+    assert (out["count"][:, :, :] == 5).all()
+    # log-sum-exp of the un-rectified sparse / dense rows
+    for h in range(cfg.heads):
+        Q, K = ro.bf16_bits_to_f64(Qb[0, h]), ro.bf16_bits_to_f64(Kb[0, h])
+        part = ro.partition(cfg.t_video, cfg.t_text, cfg.block)
+        scale = 1 / np.sqrt(cfg.head_dim)
+        for n in (0, 7, part.n_video):            # two video blocks and the text block
+            rows = part.tokens(n)
+            if n < part.n_video:
+                cols = np.concatenate([np.arange(part.starts[m], part.starts[m] + part.counts[m])
+                                       for m in np.nonzero(out["mask"][0, h, n])[0]])
+            else:
+                cols = np.arange(cfg.t_total)
+            S = Q[rows] @ K[cols].T * scale
+            want = np.log(np.exp(S - S.max(axis=1, keepdims=True)).sum(axis=1)) + S.max(axis=1)
+            np.testing.assert_allclose(out["lse"][0, h, rows], want, atol=2e-3)
+
+
+def test_mid_config_two_heads_parity(gpu):
+    """BASELINE config 1 shape (20 280 video tokens, ragged last block, block 128, d 128, 90 %)."""
+    cfg = synth.CONFIGS["mid"]
+    out, stats, _ = _run_and_compare(gpu, cfg, heads=[0, 7])
+    assert (out["count"] == 16).all()
+
+
+EDGE = {
+    "ragged_d64_b128": LayerConfig("ragged_d64_b128", 1, 2, 64, (5, 9, 13), 77, 128, 0.6),
+    "d128_b64_text": LayerConfig("d128_b64_text", 1, 2, 128, (4, 12, 10), 100, 64, 0.7),
+    "single_block": LayerConfig("single_block", 1, 1, 64, (1, 5, 7), 0, 64, 0.5),
+    "video_lt_block_text": LayerConfig("video_lt_block_text", 1, 1, 128, (1, 6, 9), 30, 128, 0.5),
+    "batch2": LayerConfig("batch2", 2, 3, 128, (3, 12, 16), 40, 128, 0.5),
+    "text_many_blocks": LayerConfig("text_many_blocks", 1, 1, 64, (2, 8, 8), 300, 64, 0.5),
+}
+
+
+@pytest.mark.parametrize("name", sorted(EDGE))
+def test_edge_shapes(gpu, name):
+    _run_and_compare(gpu, EDGE[name], seed=3)
+
+
+def test_strided_token_major_layout(gpu):
+    """Q/K/V/O stored [batch, tokens, heads, d] (strides differ from the contiguous case)."""
+    _run_and_compare(gpu, EDGE["batch2"], seed=4, layout="bthd")
+
+
+@pytest.mark.parametrize("sparsity", [0.0, 0.5, 0.95, 1.0])
+def test_sparsity_range(gpu, sparsity):
+    """rho = 0 must reproduce full attention (R = 1, nothing compensated); rho = 1 keeps one block."""
+    import parity
+    cfg = EDGE["d128_b64_text"]
+    out, stats, (Qb, Kb, Vb) = _run_and_compare(gpu, cfg, seed=5, sparsity=sparsity)
+    if sparsity == 0.0:
+        from oracle import rsa_oracle as ro
+        assert out["mask"].all()
+        np.testing.assert_allclose(out["R"], 1.0, atol=1e-5)
+        for h in range(cfg.heads):
+            Q, K, V = (ro.bf16_bits_to_f64(x[0, h]) for x in (Qb, Kb, Vb))
+            dense = ro.dense_attention(Q, K, V, 1 / np.sqrt(cfg.head_dim))
+            err = ro.bf16_bits_to_f64(out["O_bits"][0, h]) - dense
+            assert np.abs(err).max() <= parity.OUT_MAX_ABS
+            assert np.linalg.norm(err) / np.linalg.norm(dense) <= parity.OUT_REL_L2
+    if sparsity == 1.0:
+        assert (out["count"] == 1).all()
+
+
+@pytest.mark.parametrize("gapr_mode", [0, 2])
+def test_gate_modes(gpu, gapr_mode):
+    out, _, _ = _run_and_compare(gpu, EDGE["ragged_d64_b128"], seed=6, gapr_mode=gapr_mode)
+    assert out["Mc"].all() if gapr_mode == 2 else not out["Mc"].any()
+
+
+@pytest.mark.parametrize("flags", [0, 1, 2])
+def test_rectification_flags(gpu, flags):
+    _run_and_compare(gpu, EDGE["ragged_d64_b128"], seed=7, flags=flags)
+
+
+def test_forced_keep_mask(gpu):
+    """Caller-supplied adjacency mask M_adja is OR-ed into the sparse mask (Alg. 1 step 14)."""
+    cfg = EDGE["d128_b64_text"]
+    N, M = cfg.n_video_blocks, cfg.n_blocks
+    forced = np.zeros((cfg.batch, cfg.heads, N, M), dtype=bool)
+    idx = np.arange(N)
+    forced[:, :, idx, idx] = True
+    forced[:, :, idx, np.maximum(idx - 1, 0)] = True
+    out, _, _ = _run_and_compare(gpu, cfg, seed=8, forced=forced)
+    assert (out["mask"] & forced == forced).all()
+    assert (out["count"] >= 3).all()
+
+
+def test_weight_threshold_extension(gpu):
+    """p > 0 extends the kept prefix until the kept A^pool exceeds p (Alg. 1 step 13)."""
+    import parity
+    from oracle import rsa_oracle as ro
+    cfg = EDGE["d128_b64_text"]
+    p = 0.45
+    Qb, Kb, Vb = synth.make_inputs(cfg, 9)
+    out = gpu.run_layer(Qb, Kb, Vb, cfg.t_video, cfg.t_text, cfg.block, 0.9, p=p)
+    k = ro.kept_count(cfg.n_blocks, 0.9)
+    extended = 0
+    for h in range(cfg.heads):
+        ref = parity.oracle_head(Qb[0, h], Kb[0, h], Vb[0, h], cfg.t_video, cfg.t_text, cfg.block, 0.9, p=p)
+        # rows whose cumulative weight passes p by a clear margin must match exactly
+        A = ref["A_pool"]
+        srt = -np.sort(-A, axis=1)
+        cs = np.cumsum(srt, axis=1)
+        margin = np.abs(cs - p).min(axis=1)
+        clear = margin > 1e-5
+        assert clear.mean() > 0.9
+        np.testing.assert_array_equal(out["mask"][0, h][clear], ref["mask"][clear])
+        extended += int((ref["mask"].sum(axis=1) > k).sum())
+        # outputs: compare on the GPU's own masks
+        parity.compare_head(out, 0, h, dict(ref, mask=out["mask"][0, h].copy(),
+                                            R=(A * out["mask"][0, h]).sum(axis=1),
+                                            O=_oracle_output_with_mask(ref, out["mask"][0, h], Qb[0, h], Kb[0, h], Vb[0, h])),
+                            Qb[0, h], Kb[0, h], Vb[0, h], p=p)
+    assert extended > 0, "the threshold never extended a row: the case proves nothing"
+
+
+def _oracle_output_with_mask(ref, mask, Qb, Kb, Vb):
+    from oracle import rsa_oracle as ro
+    Q, K, V = (ro.bf16_bits_to_f64(x) for x in (Qb, Kb, Vb))
+    part = ref["part"]
+    O = ref["O"].copy()
+    R = (ref["A_pool"] * mask).sum(axis=1)
+    C = ro.compensation(ref["A_pool"], mask, ref["Mc"], ref["Vp"])
+    for n in range(part.n_video):
+        O[part.tokens(n)] = ro.sparse_attention_block(Q, K, V, mask[n], n, part, ref["scale"]) * R[n] + C[n][None, :]
+    return O
+
+
+def test_dense_flag_is_full_attention(gpu):
+    import parity
+    import torch
+    from oracle import rsa_oracle as ro
+    from paper_2511_19835_amd import binding as rb
+    cfg = EDGE["ragged_d64_b128"]
+    Qb, Kb, Vb = synth.make_inputs(cfg, 10)
+    Q, K, V = (gpu.bits_to_device(x) for x in (Qb, Kb, Vb))
+    buf = rb.allocate(Q, cfg.t_video, cfg.t_text, cfg.block)
+    O = torch.empty_like(Q)
+    rb.rsa_pool(buf.shape, Q, K, V, buf.Qp, buf.Kp, buf.Vp, buf.Vt, buf.Spool, buf.Apool, buf.Lmass, buf.Mc_bits,
+                0, buf.pool_ws)
+    rb.rsa_sparse_attn_rectified(buf.shape, Q, K, buf.Vt, None, None, None, None, None, None, None, rb.RSA_DENSE, O)
+    torch.cuda.synchronize()
+    Ob = gpu.device_to_bits(O)
+    for h in range(cfg.heads):
+        q, k, v = (ro.bf16_bits_to_f64(x[0, h]) for x in (Qb, Kb, Vb))
+        dense = ro.dense_attention(q, k, v, 1 / np.sqrt(cfg.head_dim))
+        err = ro.bf16_bits_to_f64(Ob[0, h]) - dense
+        assert np.abs(err).max() <= parity.OUT_MAX_ABS
+        assert np.linalg.norm(err) / np.linalg.norm(dense) <= parity.OUT_REL_L2
+
+
+def test_results_are_deterministic(gpu):
+    cfg = synth.CONFIGS["tiny"]
+    Qb, Kb, Vb = synth.make_inputs(cfg, 11)
+    a = gpu.run_layer(Qb, Kb, Vb, cfg.t_video, cfg.t_text, cfg.block, cfg.sparsity)
+    b = gpu.run_layer(Qb, Kb, Vb, cfg.t_video, cfg.t_text, cfg.block, cfg.sparsity)
+    for key in ("O_bits", "mask_words", "Mc_words", "R", "Apool", "Lmass", "count"):
+        np.testing.assert_array_equal(a[key], b[key])
