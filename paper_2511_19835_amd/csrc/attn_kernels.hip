@@ -24,6 +24,7 @@ namespace rsa {
 namespace {
 
 constexpr float kLog2e = 1.4426950408889634f;
+typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));
 
 template <int D, int BLK, int QW>
 struct AttnCfg {
@@ -33,19 +34,85 @@ struct AttnCfg {
   static constexpr int KT = BLK / 32;       // key tiles of S^T
   static constexpr int KS = D / 16;         // k-steps of K Q^T
   static constexpr int DT = D / 32;         // channel tiles of O^T
-  static constexpr int KROW = D * 2 + 16;   // bytes per K row in LDS
-  static constexpr int VROW = BLK * 2 + 16; // bytes per V^T row in LDS
-  static constexpr int LDS_BYTES = BLK * KROW + D * VROW;
+  static constexpr int KCPR = D / 8;        // 16-byte chunks per K row
+  static constexpr int VCPR = BLK / 8;      // 16-byte chunks per V^T row
+  static constexpr int KLD = BLK * KCPR / NTHR;  // chunks each thread moves per K tile
+  static constexpr int VLD = D * VCPR / NTHR;    // ... per V^T tile
+  static constexpr int NSTAGE = KLD > VLD ? KLD : VLD;
+  static constexpr int MINW = QW == 32 ? 2 : 1;  // waves per SIMD the register budget must allow
 };
 
+// LDS tiles are unpadded; the 16-byte chunk c of row r is stored at chunk position
+// c ^ key(r) so that 16 consecutive rows read at one logical chunk index hit 16 different
+// positions (all banks once). CPR = chunks per row (8 or 16).
+template <int CPR>
+__device__ inline int swizzled(int r, int c) {
+  return r * CPR + (c ^ ((r / (16 / CPR)) & (CPR - 1)));
+}
+
+// Exchange between the two half-waves (lane l <-> lane l^32) with v_permlane32_swap.
+// The vector elements are copied to scalars before the bit casts: a bit cast applied
+// directly to an element expression reads element 0 whatever the index.
+__device__ inline void half_wave_pair(float v, float& lo, float& hi) {
+  const uint32_t u = __builtin_bit_cast(uint32_t, v);
+  const auto r = __builtin_amdgcn_permlane32_swap(u, u, false, false);
+  const uint32_t r0 = r[0], r1 = r[1];
+  lo = __builtin_bit_cast(float, r0);   // value held by lane l%32
+  hi = __builtin_bit_cast(float, r1);   // value held by lane l%32 + 32
+}
+__device__ inline float half_wave_max(float v) {
+  float lo, hi;
+  half_wave_pair(v, lo, hi);
+  return fmaxf(lo, hi);
+}
+__device__ inline float half_wave_sum(float v) {
+  float lo, hi;
+  half_wave_pair(v, lo, hi);
+  return lo + hi;
+}
+
+// Tile movers. A K tile is BLK rows of the caller's K (row stride st); a V^T tile is the
+// contiguous D x BLK block rsa_pool wrote. Each thread carries NLD 16-byte chunks.
+template <class C>
+__device__ __forceinline__ void fetch_k_tile(u32x4 (&stage)[C::NSTAGE], const uint16_t* Kb, const Dims& dm, int m,
+                                             int tid) {
+  const int kv_count = dm.block_count(m);
+  const uint16_t* src = Kb + dm.block_start(m) * dm.st;
+#pragma unroll
+  for (int i = 0; i < C::KLD; ++i) {
+    const int slot = tid + i * C::NTHR;
+    int r = slot / C::KCPR;
+    const int c = slot % C::KCPR;
+    r = r < kv_count ? r : kv_count - 1;   // rows past a ragged block re-read its last row (masked later)
+    stage[i] = *reinterpret_cast<const u32x4*>(src + (int64_t)r * dm.st + c * 8);
+  }
+}
+template <class C>
+__device__ __forceinline__ void fetch_v_tile(u32x4 (&stage)[C::NSTAGE], const u32x4* src, int tid) {
+#pragma unroll
+  for (int i = 0; i < C::VLD; ++i) stage[i] = src[tid + i * C::NTHR];
+}
+template <int NLD, int CPR, int NTHR, int NS>
+__device__ __forceinline__ void park_tile(const u32x4 (&stage)[NS], u32x4* lds, int tid) {
+#pragma unroll
+  for (int i = 0; i < NLD; ++i) {
+    const int slot = tid + i * NTHR;
+    lds[swizzled<CPR>(slot / CPR, slot % CPR)] = stage[i];
+  }
+}
+
+// The running softmax reference is only raised when a row's new maximum exceeds it by
+// more than this many binades; probabilities then stay below 2^kLazyBits, which fp32 sums
+// and bf16 operands hold without loss, and the accumulators are rescaled rarely.
+constexpr float kLazyBits = 6.0f;
+
 template <int D, int BLK, int QW>
-__global__ __launch_bounds__(64 * BLK / QW) void attn_kernel(Dims dm, AttnArgs a, int n_text_items,
-                                                                        int chunk) {
+__global__ __launch_bounds__(64 * BLK / QW, (QW == 32 && BLK == 128 ? 2 : 1)) void attn_kernel(Dims dm, AttnArgs a,
+                                                                                int n_text_items, int chunk) {
   using C = AttnCfg<D, BLK, QW>;
-  __shared__ __attribute__((aligned(16))) unsigned char lds[C::LDS_BYTES];
+  __shared__ u32x4 ldsK[BLK * C::KCPR];
+  __shared__ u32x4 ldsV[D * C::VCPR];
   __shared__ float comp[2][D];
-  unsigned char* ldsK = lds;
-  unsigned char* ldsV = lds + BLK * C::KROW;
 
   // ---- which (batch*head, query block) is this workgroup ---------------------------------
   const bool dense_all = (a.flags & RSA_DENSE) != 0;
@@ -126,36 +193,29 @@ __global__ __launch_bounds__(64 * BLK / QW) void attn_kernel(Dims dm, AttnArgs a
     for (int nt = 0; nt < C::NT; ++nt)
 #pragma unroll
       for (int r = 0; r < 16; ++r) oacc[dt][nt][r] = 0.f;
-  float mrun[C::NT], lrun[C::NT];
+  float mref[C::NT], lpart[C::NT];   // softmax reference (log2 domain, scaled) and this lane's partial row sum
 #pragma unroll
-  for (int nt = 0; nt < C::NT; ++nt) { mrun[nt] = -INFINITY; lrun[nt] = 0.f; }
+  for (int nt = 0; nt < C::NT; ++nt) { mref[nt] = -INFINITY; lpart[nt] = 0.f; }
   const float cs = dm.scale * kLog2e;
 
+  u32x4 stage[C::NSTAGE];   // one tile in flight: global -> registers -> LDS
+  const u32x4* Vt4 = reinterpret_cast<const u32x4*>(Vtb);
+#define FETCH_K(m) fetch_k_tile<C>(stage, Kb, dm, (m), tid)
+#define PARK_K() park_tile<C::KLD, C::KCPR, C::NTHR>(stage, ldsK, tid)
+#define FETCH_V(m) fetch_v_tile<C>(stage, Vt4 + (size_t)(m) * (D * BLK / 8), tid)
+#define PARK_V() park_tile<C::VLD, C::VCPR, C::NTHR>(stage, ldsV, tid)
+
+  int m_cur = list ? list[0] : 0;
+  if (nlist > 0) {
+    FETCH_K(m_cur);
+    PARK_K();
+    FETCH_V(m_cur);
+  }
+
   for (int j = 0; j < nlist; ++j) {
-    const int m = list ? list[j] : j;
-    const int kv_count = dm.block_count(m);
-    const int64_t kv_t0 = dm.block_start(m);
-    __syncthreads();  // everyone is done reading the previous tiles
-    {
-      constexpr int KCH = D / 8;
-      const uint16_t* src = Kb + kv_t0 * dm.st;
-#pragma unroll 4
-      for (int idx = tid; idx < BLK * KCH; idx += C::NTHR) {
-        const int r = idx / KCH, cc = idx % KCH;
-        uint4 v = make_uint4(0, 0, 0, 0);
-        if (r < kv_count) v = *reinterpret_cast<const uint4*>(src + (int64_t)r * dm.st + cc * 8);
-        *reinterpret_cast<uint4*>(ldsK + r * C::KROW + cc * 16) = v;
-      }
-      constexpr int VCH = BLK / 8;
-      const uint16_t* vsrc = Vtb + (size_t)m * D * BLK;
-#pragma unroll 4
-      for (int idx = tid; idx < D * VCH; idx += C::NTHR) {
-        const int dd = idx / VCH, pc = idx % VCH;
-        const uint4 v = *reinterpret_cast<const uint4*>(vsrc + dd * BLK + pc * 8);
-        *reinterpret_cast<uint4*>(ldsV + dd * C::VROW + pc * 16) = v;
-      }
-    }
-    __syncthreads();
+    const int kv_count = dm.block_count(m_cur);
+    const int m_next = (j + 1 < nlist) ? (list ? list[j + 1] : j + 1) : m_cur;
+    __syncthreads();   // K tile visible; every wave is past the previous P.V (V tile free)
 
     // ---- S^T = K Q^T ------------------------------------------------------------------
     floatx16 sacc[C::KT][C::NT];
@@ -169,8 +229,7 @@ __global__ __launch_bounds__(64 * BLK / QW) void attn_kernel(Dims dm, AttnArgs a
     for (int s = 0; s < C::KS; ++s) {
 #pragma unroll
       for (int t = 0; t < C::KT; ++t) {
-        const bf16x8 ka = __builtin_bit_cast(
-            bf16x8, *reinterpret_cast<const uint4*>(ldsK + (32 * t + l32) * C::KROW + (16 * s + 8 * hf) * 2));
+        const bf16x8 ka = __builtin_bit_cast(bf16x8, ldsK[swizzled<C::KCPR>(32 * t + l32, 2 * s + hf)]);
 #pragma unroll
         for (int nt = 0; nt < C::NT; ++nt)
           sacc[t][nt] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(ka, qreg[nt][s], sacc[t][nt], 0, 0, 0);
@@ -191,6 +250,7 @@ __global__ __launch_bounds__(64 * BLK / QW) void attn_kernel(Dims dm, AttnArgs a
     }
 
     // ---- online softmax, one query column per lane -----------------------------------
+    u32x4 pb[C::KT * 2][C::NT];   // probabilities as bf16 B operands, 16 keys per entry
 #pragma unroll
     for (int nt = 0; nt < C::NT; ++nt) {
       float mx = -INFINITY;
@@ -198,65 +258,73 @@ __global__ __launch_bounds__(64 * BLK / QW) void attn_kernel(Dims dm, AttnArgs a
       for (int t = 0; t < C::KT; ++t)
 #pragma unroll
         for (int r = 0; r < 16; ++r) mx = fmaxf(mx, sacc[t][nt][r]);
-      mx = fmaxf(mx, __shfl_xor(mx, 32));
-      const float mnew = fmaxf(mrun[nt], mx);
-      const float alpha = __builtin_amdgcn_exp2f((mrun[nt] - mnew) * cs);
-      const float moff = -mnew * cs;
-      mrun[nt] = mnew;
+      mx = half_wave_max(mx) * cs;
+      if (__any(mx > mref[nt] + kLazyBits)) {
+        const float mnew = fmaxf(mref[nt], mx);
+        const float alpha = __builtin_amdgcn_exp2f(mref[nt] - mnew);
+        mref[nt] = mnew;
+        lpart[nt] *= alpha;
+#pragma unroll
+        for (int dt = 0; dt < C::DT; ++dt)
+#pragma unroll
+          for (int r = 0; r < 16; ++r) oacc[dt][nt][r] *= alpha;
+      }
+      const float moff = -mref[nt];
       float rs = 0.f;
 #pragma unroll
-      for (int t = 0; t < C::KT; ++t)
+      for (int t = 0; t < C::KT; ++t) {
+        float p[16];
 #pragma unroll
         for (int r = 0; r < 16; ++r) {
-          const float p = __builtin_amdgcn_exp2f(fmaf(sacc[t][nt][r], cs, moff));
-          sacc[t][nt][r] = p;
-          rs += p;
+          p[r] = __builtin_amdgcn_exp2f(fmaf(sacc[t][nt][r], cs, moff));
+          rs += p[r];
         }
-      rs += __shfl_xor(rs, 32);
-      lrun[nt] = lrun[nt] * alpha + rs;
 #pragma unroll
-      for (int dt = 0; dt < C::DT; ++dt)
-#pragma unroll
-        for (int r = 0; r < 16; ++r) oacc[dt][nt][r] *= alpha;
+        for (int u = 0; u < 2; ++u) {
+          u32x4 w;
+          w.x = pack_bf16x2(p[8 * u + 0], p[8 * u + 1]);
+          w.y = pack_bf16x2(p[8 * u + 2], p[8 * u + 3]);
+          w.z = pack_bf16x2(p[8 * u + 4], p[8 * u + 5]);
+          w.w = pack_bf16x2(p[8 * u + 6], p[8 * u + 7]);
+          pb[2 * t + u][nt] = w;
+        }
+      }
+      lpart[nt] += rs;
     }
+
+    PARK_V();                       // V tile of this step: registers -> LDS
+    if (j + 1 < nlist) FETCH_K(m_next);
+    __syncthreads();                // V tile visible; every wave is past this step's K reads
 
     // ---- O^T += V^T P^T ----------------------------------------------------------------
 #pragma unroll
-    for (int t = 0; t < C::KT; ++t) {
+    for (int pc = 0; pc < C::KT * 2; ++pc) {
 #pragma unroll
-      for (int u = 0; u < 2; ++u) {
-        const int pc = 2 * t + u;
-        bf16x8 pb[C::NT];
+      for (int dt = 0; dt < C::DT; ++dt) {
+        const bf16x8 va = __builtin_bit_cast(bf16x8, ldsV[swizzled<C::VCPR>(32 * dt + l32, 2 * pc + hf)]);
 #pragma unroll
-        for (int nt = 0; nt < C::NT; ++nt) {
-          uint4 w;
-          w.x = pack_bf16x2(sacc[t][nt][8 * u + 0], sacc[t][nt][8 * u + 1]);
-          w.y = pack_bf16x2(sacc[t][nt][8 * u + 2], sacc[t][nt][8 * u + 3]);
-          w.z = pack_bf16x2(sacc[t][nt][8 * u + 4], sacc[t][nt][8 * u + 5]);
-          w.w = pack_bf16x2(sacc[t][nt][8 * u + 6], sacc[t][nt][8 * u + 7]);
-          pb[nt] = __builtin_bit_cast(bf16x8, w);
-        }
-#pragma unroll
-        for (int dt = 0; dt < C::DT; ++dt) {
-          const bf16x8 va = __builtin_bit_cast(
-              bf16x8, *reinterpret_cast<const uint4*>(ldsV + (32 * dt + l32) * C::VROW + (16 * pc + 8 * hf) * 2));
-#pragma unroll
-          for (int nt = 0; nt < C::NT; ++nt)
-            oacc[dt][nt] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(va, pb[nt], oacc[dt][nt], 0, 0, 0);
-        }
+        for (int nt = 0; nt < C::NT; ++nt)
+          oacc[dt][nt] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(va, __builtin_bit_cast(bf16x8, pb[pc][nt]),
+                                                                 oacc[dt][nt], 0, 0, 0);
       }
     }
+    if (j + 1 < nlist) {
+      PARK_K();                     // next K tile: registers -> LDS (visible after the barrier that opens the next step)
+      FETCH_V(m_next);
+    }
+    m_cur = m_next;
   }
 
   // ---- epilogue: normalise, rectify, compensate, store ------------------------------------
-  __syncthreads();   // comp[] is complete (and nobody still reads the tiles)
+  __syncthreads();   // comp[] is complete
   const float rfac = (sparse_row && (a.flags & RSA_RECTIFY_CRITICAL)) ? a.R[vrow] : 1.0f;
   uint16_t* Ob = a.O + base;
 #pragma unroll
   for (int nt = 0; nt < C::NT; ++nt) {
+    const float lsum = half_wave_sum(lpart[nt]);
     const int q = wave * QW + 32 * nt + l32;
     if (q >= q_count) continue;
-    const float f = rfac / lrun[nt];
+    const float f = rfac / lsum;
     uint16_t* orow = Ob + (q_t0 + q) * dm.st;
 #pragma unroll
     for (int dt = 0; dt < C::DT; ++dt)
@@ -275,8 +343,12 @@ __global__ __launch_bounds__(64 * BLK / QW) void attn_kernel(Dims dm, AttnArgs a
         *reinterpret_cast<uint2*>(orow + d0) = w;
       }
     if (a.lse && hf == 0)
-      a.lse[((size_t)bh * dm.t) + q_t0 + q] = mrun[nt] * dm.scale + logf(lrun[nt]);
+      a.lse[((size_t)bh * dm.t) + q_t0 + q] = (mref[nt] + log2f(lsum)) * 0.6931471805599453f;
   }
+#undef FETCH_K
+#undef PARK_K
+#undef FETCH_V
+#undef PARK_V
 }
 
 template <int D, int BLK, int QW>
