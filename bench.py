@@ -12,7 +12,6 @@ stream with the inputs already resident in HBM. Default workload: the HunyuanVid
 from __future__ import annotations
 
 import argparse
-import concurrent.futures
 import json
 import os
 import sys
@@ -29,25 +28,12 @@ PEAK_BF16_MFMA_TFLOPS = 2500.0     # MI355X dense bf16 MFMA
 PEAK_HBM_GBS = 8000.0              # MI355X HBM3E
 
 
-def _gen_head(args):
-    cfg, seed, b, h = args
-    return synth.make_head(cfg, seed, b, h)
-
-
-def generate_inputs(cfg, seed, workers=8):
-    shape = (cfg.batch, cfg.heads, cfg.t_total, cfg.head_dim)
-    Q, K, V = (np.empty(shape, dtype=np.uint16) for _ in range(3))
-    jobs = [(cfg, seed, b, h) for b in range(cfg.batch) for h in range(cfg.heads)]
-    with concurrent.futures.ProcessPoolExecutor(max_workers=workers) as ex:
-        for (c, s, b, h), (q, k, v) in zip(jobs, ex.map(_gen_head, jobs)):
-            Q[b, h], K[b, h], V[b, h] = q, k, v
-    return Q, K, V
-
-
-def cpu_baseline(cfg, sparsity, Qb, Kb, Vb, gpu_O_bits, budget_s=15.0):
+def cpu_baseline(cfg, sparsity, Qb, Kb, Vb, gpu_O_bits, gpu_mask, gpu_Mc, budget_s=15.0):
     """Time the oracle, as it stands, on the host cores for a bounded sample of the same
-    workload (head 0: pooled stages in full, then query blocks spread over the sequence
-    until the time budget is used), and compare the GPU output on exactly those blocks."""
+    workload (head 0: pooled stages in full, then query blocks in a seeded random order
+    until the time budget is used), and compare the GPU output on exactly those blocks.
+    Where the GPU's gate bit of a block differs from the oracle's inside the tolerance band
+    (gain and error within 1e-3 relative), the comparison uses the GPU's bit, as the tests do."""
     sys.path.insert(0, os.path.join(ROOT, "tests"))
     from oracle import rsa_oracle as ro
     import parity
@@ -67,7 +53,7 @@ def cpu_baseline(cfg, sparsity, Qb, Kb, Vb, gpu_O_bits, budget_s=15.0):
     t_pooled = time.perf_counter() - t0
 
     # query blocks: text blocks first (dense rows), then video blocks spread evenly
-    order = list(range(N, M)) + [int(x) for x in np.unique(np.linspace(0, N - 1, 64).astype(int))]
+    order = list(range(N, M)) + [int(x) for x in np.random.default_rng(0).permutation(N)]
     O_ref = np.full((cfg.t_total, d), np.nan)
     done, rows_done, t_blocks = [], 0, 0.0
     flops_done = 0.0
@@ -93,12 +79,21 @@ def cpu_baseline(cfg, sparsity, Qb, Kb, Vb, gpu_O_bits, budget_s=15.0):
     dense_flop = 4.0 * cfg.t_total ** 2 * d * cfg.heads * cfg.batch
 
     # parity of the GPU output on the sampled blocks (same bar as the tests)
+    mcdiff = gpu_Mc != Mc
+    rel_gap = np.abs(G - E) / np.maximum(np.maximum(G, E), 1e-300)
+    gate_ok = bool(np.all(rel_gap[mcdiff] <= parity.GATE_BAND))
+    mask_same = bool((gpu_mask == mask).all())
+    for n in done:
+        if n < N and (mcdiff[n] & ~mask[n]).any():
+            O_ref[part.tokens(n)] += ((A_pool[n] * (~mask[n] & gpu_Mc[n])) @ Vp - C[n])[None, :]
     rows = np.concatenate([np.arange(part.starts[n], part.starts[n] + part.counts[n]) for n in done])
     err = ro.bf16_bits_to_f64(gpu_O_bits[rows]) - O_ref[rows]
     par = dict(max_abs=float(np.abs(err).max()),
                rel_l2=float(np.linalg.norm(err) / np.linalg.norm(O_ref[rows])),
-               rows=int(rows.size), bar_max_abs=parity.OUT_MAX_ABS, bar_rel_l2=parity.OUT_REL_L2)
-    par["ok"] = bool(par["max_abs"] <= parity.OUT_MAX_ABS and par["rel_l2"] <= parity.OUT_REL_L2)
+               rows=int(rows.size), bar_max_abs=parity.OUT_MAX_ABS, bar_rel_l2=parity.OUT_REL_L2,
+               mask_identical=mask_same, gate_bits_differing=int(mcdiff.sum()), gate_diffs_inside_band=gate_ok)
+    par["ok"] = bool(par["max_abs"] <= parity.OUT_MAX_ABS and par["rel_l2"] <= parity.OUT_REL_L2
+                     and mask_same and gate_ok)
     try:
         import threadpoolctl
         threads = max(p["num_threads"] for p in threadpoolctl.threadpool_info())
@@ -137,7 +132,7 @@ def main():
 
     # worker processes are forked here, before anything touches the GPU
     t0 = time.perf_counter()
-    Qb, Kb, Vb = generate_inputs(cfg, args.seed, workers=min(16, os.cpu_count() or 8))
+    Qb, Kb, Vb = synth.make_inputs(cfg, args.seed, workers=min(16, os.cpu_count() or 8))
     t_gen = time.perf_counter() - t0
 
     import torch
@@ -244,9 +239,9 @@ def main():
 
     if not args.no_cpu_baseline:
         O_head0 = harness.device_to_bits(O[0, 0])
-        base, par, ref = cpu_baseline(cfg, sparsity, Qb[0, 0], Kb[0, 0], Vb[0, 0], O_head0)
         gmask = harness.unpack_bits(buf.mask_bits[0, 0].cpu().numpy(), M)
-        par["mask_rows_differing"] = int((gmask != ref["mask"]).any(axis=1).sum())
+        gmc = harness.unpack_bits(buf.Mc_bits[0, 0].cpu().numpy(), M)
+        base, par, ref = cpu_baseline(cfg, sparsity, Qb[0, 0], Kb[0, 0], Vb[0, 0], O_head0, gmask, gmc)
         out["cpu_baseline"] = base
         out["parity_sample"] = par
     print(json.dumps(out))

@@ -20,10 +20,10 @@ __device__ inline void accumulate8(float (&acc)[8], const uint4& v) {
 }
 
 // Reduce the per-thread partial sums over the row groups and write the block mean
-// (fp32) and, optionally, its split into two bf16 terms hi + lo.
+// (fp32) and, optionally, a bf16 copy.
 template <int D, int RPP>
 __device__ inline void finish_mean(float (*red)[D], const float (&acc)[8], int r0, int cc, int count,
-                                   float* mean_out, uint16_t* hl_out) {
+                                   float* mean_out, uint16_t* bf_out) {
 #pragma unroll
   for (int e = 0; e < 8; ++e) red[r0][cc * 8 + e] = acc[e];
   __syncthreads();
@@ -34,11 +34,7 @@ __device__ inline void finish_mean(float (*red)[D], const float (&acc)[8], int r
     for (int r = 0; r < RPP; ++r) s += red[r][tid];
     const float mean = s / (float)count;
     mean_out[tid] = mean;
-    if (hl_out) {
-      const uint16_t hi = to_bf16_bits(mean);
-      hl_out[tid] = hi;
-      hl_out[D + tid] = to_bf16_bits(mean - bf16_bits_to_float(hi));
-    }
+    if (bf_out) bf_out[tid] = to_bf16_bits(mean);
   }
 }
 
@@ -69,10 +65,10 @@ __global__ __launch_bounds__(256) void pool_qk_kernel(Dims dm, PoolArgs a) {
 
   if (which == 0) {
     const size_t row = (size_t)bh * dm.n + m;
-    finish_mean<D, RPP>(red, acc, r0, cc, count, a.Qp + row * D, a.QpHL ? a.QpHL + row * 2 * D : nullptr);
+    finish_mean<D, RPP>(red, acc, r0, cc, count, a.Qp + row * D, a.Qpb ? a.Qpb + row * D : nullptr);
   } else {
     const size_t row = (size_t)bh * dm.m + m;
-    finish_mean<D, RPP>(red, acc, r0, cc, count, a.Kp + row * D, a.KpHL ? a.KpHL + row * 2 * D : nullptr);
+    finish_mean<D, RPP>(red, acc, r0, cc, count, a.Kp + row * D, a.Kpb ? a.Kpb + row * D : nullptr);
   }
 }
 

@@ -43,14 +43,14 @@ inline size_t align256(size_t x) { return (x + 255) & ~(size_t)255; }
 
 // Carving of the pooling workspace; every piece 256-byte aligned.
 struct PoolWs {
-  size_t qphl, kphl, da, dbt, total;
+  size_t qpb, kpb, da, dbt, total;
 };
 PoolWs pool_ws_layout(const Dims& d) {
   size_t bh = (size_t)d.batch * d.heads;
   PoolWs w;
   size_t off = 0;
-  w.qphl = off; off += align256(bh * d.n * 2 * d.d * sizeof(uint16_t));
-  w.kphl = off; off += align256(bh * d.m * 2 * d.d * sizeof(uint16_t));
+  w.qpb = off; off += align256(bh * d.n * d.d * sizeof(uint16_t));
+  w.kpb = off; off += align256(bh * d.m * d.d * sizeof(uint16_t));
   w.da = off;   off += align256(bh * (size_t)d.n * d.m * sizeof(float));
   w.dbt = off;  off += align256(bh * (size_t)d.n * d.m * sizeof(float));
   w.total = off;
@@ -99,8 +99,8 @@ int rsa_pool(const rsa_shape* shape, const void* Q, const void* K, const void* V
   rsa::PoolArgs pa;
   pa.Q = (const uint16_t*)Q; pa.K = (const uint16_t*)K; pa.V = (const uint16_t*)V;
   pa.Qp = Qp; pa.Kp = Kp; pa.Vp = Vp; pa.Vt = (uint16_t*)Vt;
-  pa.QpHL = (uint16_t*)(wsb + wl.qphl);
-  pa.KpHL = (uint16_t*)(wsb + wl.kphl);
+  pa.Qpb = (uint16_t*)(wsb + wl.qpb);
+  pa.Kpb = (uint16_t*)(wsb + wl.kpb);
   if (rsa::launch_pool(d, pa, s) != hipSuccess) return RSA_E_LAUNCH;
 
   rsa::ScoreArgs sa;
@@ -110,7 +110,7 @@ int rsa_pool(const rsa_shape* shape, const void* Q, const void* K, const void* V
 
   rsa::GaprArgs ga;
   ga.Q = (const uint16_t*)Q; ga.K = (const uint16_t*)K;
-  ga.QpHL = pa.QpHL; ga.KpHL = pa.KpHL; ga.Spool = Spool;
+  ga.Qpb = pa.Qpb; ga.Kpb = pa.Kpb; ga.Spool = Spool;
   ga.DA = (float*)(wsb + wl.da); ga.DBt = (float*)(wsb + wl.dbt);
   ga.Mc_bits = Mc_bits; ga.mode = gapr_mode;
   if (rsa::launch_gapr(d, ga, s) != hipSuccess) return RSA_E_LAUNCH;

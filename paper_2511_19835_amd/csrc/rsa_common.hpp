@@ -50,7 +50,7 @@ struct PoolArgs {
   const uint16_t *Q, *K, *V;
   float *Qp, *Kp, *Vp;
   uint16_t* Vt;
-  uint16_t *QpHL, *KpHL;   // optional [.., 2, d] bf16 hi/lo split of the pooled vectors
+  uint16_t *Qpb, *Kpb;     // optional bf16 copies of the pooled vectors (operands of the gate GEMMs)
 };
 hipError_t launch_pool(const Dims& dm, const PoolArgs& a, hipStream_t s);
 
@@ -63,7 +63,7 @@ hipError_t launch_scores(const Dims& dm, const ScoreArgs& a, hipStream_t s);
 
 struct GaprArgs {
   const uint16_t *Q, *K;
-  const uint16_t *QpHL, *KpHL;
+  const uint16_t *Qpb, *Kpb;
   const float* Spool;
   float *DA, *DBt;         // [b][h][N][M], [b][h][M][N]
   uint32_t* Mc_bits;

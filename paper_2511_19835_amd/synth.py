@@ -142,21 +142,38 @@ def make_head(cfg: LayerConfig, seed: int, b: int, h: int,
     return f32_to_bf16_bits(q), f32_to_bf16_bits(k), f32_to_bf16_bits(v)
 
 
-def make_inputs(cfg: LayerConfig, seed: int = 0, heads: Optional[Iterable[int]] = None):
+def _make_head_job(job):
+    cfg, seed, b, h = job
+    return make_head(cfg, seed, b, h)
+
+
+def make_inputs(cfg: LayerConfig, seed: int = 0, heads: Optional[Iterable[int]] = None, workers: int = 1,
+                threads: bool = False):
     """Q, K, V as uint16 bf16 bit patterns, shape [batch, len(heads), t_total, head_dim].
 
     ``heads`` selects a subset of head indices (each head has its own generator stream,
-    so a subset reproduces exactly the same bits as the full draw).
+    so a subset reproduces exactly the same bits as the full draw). ``workers`` > 1 draws
+    heads in forked worker processes (call it before the process touches the GPU) or, with
+    ``threads=True``, in threads of this process.
     """
     hs = list(range(cfg.heads)) if heads is None else list(heads)
-    coords = tile_order_coords(cfg.grid, cfg.block)
     shape = (cfg.batch, len(hs), cfg.t_total, cfg.head_dim)
     Q = np.empty(shape, dtype=np.uint16)
     K = np.empty(shape, dtype=np.uint16)
     V = np.empty(shape, dtype=np.uint16)
+    jobs = [(cfg, seed, b, h) for b in range(cfg.batch) for h in hs]
+    if workers > 1 and len(jobs) > 1:
+        import concurrent.futures
+        pool = concurrent.futures.ThreadPoolExecutor if threads else concurrent.futures.ProcessPoolExecutor
+        with pool(max_workers=min(workers, len(jobs))) as ex:
+            results = list(ex.map(_make_head_job, jobs))
+    else:
+        coords = tile_order_coords(cfg.grid, cfg.block)
+        results = [make_head(cfg, seed, b, h, coords) for (_, _, b, h) in jobs]
+    it = iter(results)
     for b in range(cfg.batch):
-        for i, h in enumerate(hs):
-            Q[b, i], K[b, i], V[b, i] = make_head(cfg, seed, b, h, coords)
+        for i in range(len(hs)):
+            Q[b, i], K[b, i], V[b, i] = next(it)
     return Q, K, V
 
 

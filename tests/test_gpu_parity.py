@@ -210,3 +210,30 @@ def test_results_are_deterministic(gpu):
     b = gpu.run_layer(Qb, Kb, Vb, cfg.t_video, cfg.t_text, cfg.block, cfg.sparsity)
     for key in ("O_bits", "mask_words", "Mc_words", "R", "Apool", "Lmass", "count"):
         np.testing.assert_array_equal(a[key], b[key])
+
+
+def test_full_size_hunyuan_shape_sampled(gpu):
+    """BASELINE config 3 at full size (24 heads, 118 800 video + 256 text tokens, block 128,
+    90 %), in the launch configuration the benchmark times. All pooled tensors, masks, gates
+    and factors of two heads are compared in full; outputs on sampled query blocks (first,
+    ragged last video block, both text blocks, 12 random); cheap properties on every head."""
+    import parity
+    from paper_2511_19835_amd import binding as rb
+    import torch
+    cfg = synth.CONFIGS["hunyuan"]
+    Qb, Kb, Vb = synth.make_inputs(cfg, 0, workers=8, threads=True)   # the GPU is initialised: no forking here
+    out = gpu.run_layer(Qb, Kb, Vb, cfg.t_video, cfg.t_text, cfg.block, cfg.sparsity, want_lse=False)
+    N, M = cfg.n_video_blocks, cfg.n_blocks
+    assert (out["count"] == 94).all()
+    assert (out["mask"].sum(axis=-1) == 94).all()
+    assert np.all((out["R"] > 0) & (out["R"] <= 1 + 1e-5))
+    np.testing.assert_allclose(out["Apool"].sum(axis=-1), 1.0, atol=2e-5)
+    from oracle import rsa_oracle as ro
+    assert np.isfinite(ro.bf16_bits_to_f64(out["O_bits"])).all()
+    rng = np.random.default_rng(0)
+    for h in (0, 17):
+        blocks = sorted(set([0, N - 1, N, N + 1] + [int(x) for x in rng.integers(0, N, 12)]))
+        ref = parity.oracle_head(Qb[0, h], Kb[0, h], Vb[0, h], cfg.t_video, cfg.t_text, cfg.block, cfg.sparsity,
+                                 query_blocks=blocks)
+        st = parity.compare_head(out, 0, h, ref, Qb[0, h], Kb[0, h], Vb[0, h], query_blocks=blocks)
+        print(f"  [hunyuan h{h}] {st}", flush=True)
