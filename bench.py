@@ -107,6 +107,17 @@ def cpu_baseline(cfg, sparsity, Qb, Kb, Vb, gpu_O_bits, gpu_mask, gpu_Mc, budget
     return base, par, dict(mask=mask, A_pool=A_pool, R=R, Mc=Mc)
 
 
+# Fabric bytes per attn_kernel launch from rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE runs of this file
+# (counter KiB x 1024 x the scale the same counter shows for a plain copy kernel: 2.0 fetch, 1.0 write).
+# A counter run cannot be made from inside the timed process, so the figure is carried here for the
+# exact workloads it was taken on and is null for any other.
+MEASURED_TRAFFIC_BYTES = {("hunyuan", 0.9, 0, 24): 50.39e6 * 2.0 * 1024 + 716.6e3 * 1024}
+
+
+def measured_traffic(cfg, sparsity, args):
+    return MEASURED_TRAFFIC_BYTES.get((cfg.name, round(float(sparsity), 6), args.seed, cfg.heads))
+
+
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
@@ -119,6 +130,9 @@ def main():
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-dense", action="store_true")
     ap.add_argument("--dense-steps", type=int, default=1)
+    ap.add_argument("--copy-calibration", action="store_true",
+                    help="also run one plain elementwise copy of Q (read |Q| bytes, write |Q| bytes): the kernel "
+                         "the FETCH_SIZE / WRITE_SIZE counters of a rocprofv3 --pmc run are scaled against")
     args = ap.parse_args()
     if args.gpus != 1:
         sys.exit("bench.py: this build runs on ONE GPU; every (batch, head) is independent, so more GPUs "
@@ -206,7 +220,8 @@ def main():
         "roofline": {
             "kernel": "attn_kernel (rsa_sparse_attn_rectified)", "bound": "mfma",
             "achieved": attn_tflops, "peak": PEAK_BF16_MFMA_TFLOPS, "unit": "TFLOP/s",
-            "frac": attn_tflops / PEAK_BF16_MFMA_TFLOPS, "traffic": None,
+            "frac": attn_tflops / PEAK_BF16_MFMA_TFLOPS,
+            "traffic": measured_traffic(cfg, sparsity, args),
             "flop_per_launch": crit_flop, "critical_tile_pairs": pairs, "ms": attn_ms,
         },
         "roofline_pool": {
@@ -219,6 +234,16 @@ def main():
                          "on one NVIDIA H100 PCIe, CUDA 12.4; no per-layer figure",
         "input_generation_s": round(t_gen, 1),
     }
+
+    if args.copy_calibration:
+        src = Q.view(torch.int16)
+        dst = torch.empty_like(src)
+        torch.cuda.synchronize()
+        torch.bitwise_or(src, 0, out=dst)        # one elementwise kernel, nothing else touches these buffers
+        torch.cuda.synchronize()
+        out["copy_calibration"] = {"kernel": "elementwise bitwise_or(Q, 0)", "bytes_read": src.numel() * 2,
+                                   "bytes_written": src.numel() * 2}
+        del dst
 
     if not args.no_dense:
         rb.rsa_sparse_attn_rectified(buf.shape, Q, K, buf.Vt, None, None, None, None, None, None, None,

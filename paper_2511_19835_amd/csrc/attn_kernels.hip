@@ -4,22 +4,25 @@
 // One workgroup per (batch*head, query block), one wave per 32 query rows. Video query
 // blocks walk their compact, ascending list of critical key blocks; text query blocks
 // (and every block under RSA_DENSE) walk all M key blocks. Key blocks are consumed in steps
-// of 64 keys. For each step the K rows [64][d] and the channel-major V rows [d][64] are
-// brought into LDS by direct-to-LDS loads (global_load_lds_dwordx4: no staging registers),
-// double-buffered, issued one whole step ahead; one barrier per step hands the buffers
+// of KVS keys. For each step the K rows [KVS][d] and the channel-major V rows [d][KVS] are
+// brought into LDS by direct-to-LDS loads (global_load_lds_dwordx4: no staging registers)
+// into a ring of NSTAGE buffers, requested NSTAGE-1 steps ahead so that enough bytes are in
+// flight to cover the latency of the L2-miss path; one barrier per step hands a buffer
 // over. Each wave then computes, with v_mfma_f32_32x32x16_bf16,
 //     S^T = K Q^T      (M = key, N = query, k = channel)      -> accumulators: one query
 //     O^T += V^T P^T   (M = channel, N = query, k = key)         column per lane
 // so the online softmax is lane-local except for one exchange between the two half-waves,
 // and the probabilities a lane holds after the first product are exactly the B operand it
 // needs for the second (rsa_pool stores V in that key order).
-// Epilogue: O = R_n * acc / l + C_n with C_n = sum_{m: not kept and M_c} A^pool[n][m] v^pool_m.
+// Epilogue: O = R_n * acc / l + C_n, C_n = sum_{m: not kept and M_c} A^pool[n][m] v^pool_m
+// (computed beforehand by compensation_kernel into the workspace).
 //
-// MFMA-bound by design: 4*B*B*d flop per (query block, key block) pair against 2*B*d*2
-// bytes of K/V traffic that is meant to come from L2 / Infinity Cache: workgroups that run
-// at the same time work on neighbouring query blocks of the same head, and each XCD
-// (workgroup id modulo 8) owns a contiguous range of query blocks. Two workgroups share a
-// CU (64 KB of LDS and at most 256 VGPRs each) so one's softmax overlaps the other's MFMAs.
+// 4*B*B*d flop per (query block, key block) pair against 2*B*d*2 bytes of K/V traffic.
+// Critical-block lists of neighbouring query blocks overlap little, so most of that
+// traffic misses the 4 MB L2 of an XCD and is served by the Infinity Cache / HBM path:
+// the kernel lives on keeping many tile loads in flight. Workgroups are ordered so that
+// the long dense text rows start first and each XCD (workgroup id modulo 8) owns a
+// contiguous range of query blocks; two workgroups share a CU.
 #include "rsa_common.hpp"
 
 namespace rsa {
@@ -27,12 +30,21 @@ namespace {
 
 constexpr float kLog2e = 1.4426950408889634f;
 typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));
-constexpr int KVS = 64;   // keys per step
+#ifndef RSA_KVS
+#define RSA_KVS 64
+#endif
+#ifndef RSA_NSTAGE
+#define RSA_NSTAGE 2
+#endif
+#ifndef NSPLIT
+#define NSPLIT 1
+#endif
+constexpr int KVS = RSA_KVS;        // keys per step
+constexpr int NSTAGE = RSA_NSTAGE;  // LDS ring depth
 
 template <int D, int BLK>
 struct AttnCfg {
-  static constexpr int QW = 32;             // query rows per wave
-  static constexpr int NW = BLK / QW;       // waves per workgroup
+  static constexpr int NW = BLK / 32;       // waves per workgroup (one per 32 query rows)
   static constexpr int NTHR = 64 * NW;
   static constexpr int SPB = BLK / KVS;     // steps per key block
   static constexpr int KT = KVS / 32;       // key tiles of S^T per step
@@ -45,7 +57,11 @@ struct AttnCfg {
   static constexpr int VINST = D * VCPR / 64;     // ... per V^T step tile
   static constexpr int KPW = KINST / NW;    // per wave
   static constexpr int VPW = VINST / NW;
+  static constexpr int KBUF = KVS * KCPR;   // 16-byte chunks per K buffer
+  static constexpr int VBUF = D * VCPR;     // ... per V^T buffer
+  static constexpr int STAGE = KBUF + VBUF; // one ring stage
   static_assert(KINST % NW == 0 && VINST % NW == 0, "loads must split evenly over the waves");
+  static_assert(NSTAGE >= 2 && NSTAGE * STAGE * 16 <= 80 * 1024, "ring must leave room for a second workgroup per CU");
 };
 
 // LDS tiles are unpadded; the 16-byte chunk c of row r is stored at chunk position
@@ -83,13 +99,19 @@ __device__ __forceinline__ float half_wave_sum(float v) {
 // barrier that publishes the buffer, and `fence` names the LDS buffer so that it counts as
 // written. Two address forms: scalar base + per-lane 32-bit byte offset, and per-lane pointer.
 __device__ __forceinline__ void dma16_sv(uint32_t lds_addr, const void* sbase, uint32_t voff, void* fence) {
+  // the base is wave-uniform by construction; make sure it sits in an SGPR pair
+  const uint64_t p = (uint64_t)(uintptr_t)sbase;
+  // (the builtin returns a signed int: widen through uint32_t, or the low word sign-extends)
+  const uint32_t p_lo = (uint32_t)__builtin_amdgcn_readfirstlane((uint32_t)p);
+  const uint32_t p_hi = (uint32_t)__builtin_amdgcn_readfirstlane((uint32_t)(p >> 32));
+  const uint64_t ps = ((uint64_t)p_hi << 32) | (uint64_t)p_lo;
   asm volatile("s_mov_b32 m0, %0\n\tglobal_load_lds_dwordx4 %1, %2"
-               ::"s"(lds_addr), "v"(voff), "s"(sbase), "r"(fence) : "memory");
+               ::"s"(__builtin_amdgcn_readfirstlane(lds_addr)), "v"(voff), "s"(ps), "r"(fence) : "memory");
 }
 __device__ __forceinline__ void dma16_v(uint32_t lds_addr, const void* gptr, void* fence) {
-  asm volatile("s_mov_b32 m0, %0\n\tglobal_load_lds_dwordx4 %1, off" ::"s"(lds_addr), "v"(gptr), "r"(fence) : "memory");
+  asm volatile("s_mov_b32 m0, %0\n\tglobal_load_lds_dwordx4 %1, off"
+               ::"s"(__builtin_amdgcn_readfirstlane(lds_addr)), "v"(gptr), "r"(fence) : "memory");
 }
-__device__ __forceinline__ void wait_all_loads() { __builtin_amdgcn_s_waitcnt(0x0F70); }   // vmcnt(0)
 
 // The running softmax reference is only raised when a row's new maximum exceeds it by
 // more than this many binades; probabilities then stay below 2^kLazyBits, which fp32 sums
@@ -99,13 +121,18 @@ constexpr float kLazyBits = 6.0f;
 template <int V>
 struct IntC { static constexpr int value = V; };
 
+template <int NLEFT>
+__device__ __forceinline__ void wait_loads_leaving() {
+  // vmcnt(NLEFT): bits 3:0 and 15:14 hold the count, exp/lgkm fields stay at "no wait"
+  __builtin_amdgcn_s_waitcnt(0x0F70 | (NLEFT & 15) | ((NLEFT >> 4) << 14));
+}
+
 template <int D, int BLK>
-__global__ __launch_bounds__(64 * BLK / 32, (BLK == 128 ? 2 : 1)) void attn_kernel(Dims dm, AttnArgs a, int n_text_items, int chunk) {
+__global__ __launch_bounds__(64 * BLK / 32, (BLK == 128 ? 2 : 1)) void attn_kernel(Dims dm, AttnArgs a, int n_text_items,
+                                                                                  int chunk) {
   using C = AttnCfg<D, BLK>;
-  constexpr int KBUF = KVS * C::KCPR, VBUF = D * C::VCPR;    // 16-byte chunks per buffer
-  __shared__ u32x4 ldsK[2 * KBUF];
-  __shared__ u32x4 ldsV[2 * VBUF];
-  __shared__ float comp[2][D];
+  constexpr int KBUF = C::KBUF, VBUF = C::VBUF;
+  __shared__ u32x4 lds[NSTAGE * C::STAGE];      // ring: stage st = [K rows | V^T rows]
 
   // ---- which (batch*head, query block) is this workgroup ---------------------------------
   const bool dense_all = (a.flags & RSA_DENSE) != 0;
@@ -121,7 +148,7 @@ __global__ __launch_bounds__(64 * BLK / 32, (BLK == 128 ? 2 : 1)) void attn_kern
       const int xcd = v & 7, j = v >> 3;
       bh = j / chunk;
       qb = xcd * chunk + j % chunk;
-      if (qb >= dm.n) return;
+      if (qb >= dm.n) return;          // whole workgroup leaves before any barrier
     }
   }
   const int b = bh / dm.heads, h = bh % dm.heads;
@@ -139,81 +166,78 @@ __global__ __launch_bounds__(64 * BLK / 32, (BLK == 128 ? 2 : 1)) void attn_kern
   const uint16_t* Kb = a.K + base;
   const uint16_t* Vtb = a.Vt + (size_t)bh * dm.m * D * BLK;
 
-  // ---- pooled compensation C_n (Alg. 1 step 21), parked in LDS for the epilogue ----------
-  const bool do_comp = sparse_row && (a.flags & RSA_COMPENSATE);
-  if (do_comp) {
-    constexpr int G = C::NTHR / D;                 // thread groups striding over mask words
-    const int dd = tid % D, g = tid / D;
-    float accv = 0.f;
-    if (g < 2) {
-      const uint32_t* mk = a.mask_bits + vrow * dm.w;
-      const uint32_t* mc = a.Mc_bits + vrow * dm.w;
-      const float* Ap = a.Apool + vrow * dm.m;
-      const float* Vp = a.Vp + (size_t)bh * dm.m * D;
-      constexpr int GS = G < 2 ? G : 2;
-      for (int wd = g; wd < dm.w; wd += GS) {
-        uint32_t bits = ~mk[wd] & mc[wd];
-        while (bits) {
-          const int bit = __builtin_ctz(bits);
-          bits &= bits - 1;
-          const int m = wd * 32 + bit;
-          accv = fmaf(Ap[m], Vp[(size_t)m * D + dd], accv);
-        }
-      }
-      comp[g][dd] = accv;
-    }
-    if (G < 2 && tid < D) comp[1][tid] = 0.f;
-  }
-
-  // ---- loop-invariant per-lane pieces of the direct-to-LDS loads --------------------------
-  // Load i of a K step tile fills LDS rows [i*RK, (i+1)*RK); wave w issues loads w*KPW + ii.
+  // ---- direct-to-LDS loads ---------------------------------------------------------------
+  // A load fills 1 KB of LDS = RK consecutive K rows (RV consecutive V^T rows). Load ii of
+  // wave w covers rows pass*ROWS_PER_PASS + (class*NW + w)*RK + (lane / chunks-per-row): the
+  // swizzle key of a lane's row then depends on the class only, so KOFF (usually 1) per-lane
+  // byte offsets serve all of a wave's loads and everything else is scalar.
   constexpr int RK = 64 / C::KCPR, RV = 64 / C::VCPR;
-  int k_row[C::KPW], k_col[C::KPW];
-  uint32_t k_voff[C::KPW], v_voff[C::VPW];       // byte offsets from the step's scalar base
+  constexpr int KOFF = (C::NW * RK >= 16) ? 1 : 16 / (C::NW * RK);
+  constexpr int VOFF = (C::NW * RV >= 16) ? 1 : 16 / (C::NW * RV);
+  static_assert(C::KPW % KOFF == 0 && C::VPW % VOFF == 0, "row classes must divide a wave's loads");
+  int k_r0[KOFF], k_col[KOFF];
+  uint32_t k_voff[KOFF], v_voff[VOFF];
 #pragma unroll
-  for (int ii = 0; ii < C::KPW; ++ii) {
-    const int r = (wave * C::KPW + ii) * RK + lane / C::KCPR;
-    k_row[ii] = r;
-    k_col[ii] = ((lane % C::KCPR) ^ swz_key<C::KCPR>(r)) * 8;
-    k_voff[ii] = (uint32_t)((r * dm.st + k_col[ii]) * 2);
+  for (int c = 0; c < KOFF; ++c) {
+    k_r0[c] = (c * C::NW + wave) * RK + lane / C::KCPR;
+    k_col[c] = ((lane % C::KCPR) ^ swz_key<C::KCPR>(k_r0[c])) * 8;              // element offset in the row
+    k_voff[c] = (uint32_t)((k_r0[c] * dm.st + k_col[c]) * 2);
   }
 #pragma unroll
-  for (int ii = 0; ii < C::VPW; ++ii) {
-    const int dd = (wave * C::VPW + ii) * RV + lane / C::VCPR;
-    v_voff[ii] = (uint32_t)((dd * BLK + ((lane % C::VCPR) ^ swz_key<C::VCPR>(dd)) * 8) * 2);
+  for (int c = 0; c < VOFF; ++c) {
+    const int r0 = (c * C::NW + wave) * RV + lane / C::VCPR;
+    v_voff[c] = (uint32_t)((r0 * BLK + ((lane % C::VCPR) ^ swz_key<C::VCPR>(r0)) * 8) * 2);
   }
-  const uint32_t ldsK_addr = (uint32_t)(uintptr_t)&ldsK[0] + wave * C::KPW * 1024;
-  const uint32_t ldsV_addr = (uint32_t)(uintptr_t)&ldsV[0] + wave * C::VPW * 1024;
+  constexpr int K_ROWS_PER_PASS = C::NW * RK * KOFF, V_ROWS_PER_PASS = C::NW * RV * VOFF;
+  constexpr int K_LDS_CLASS = C::NW * RK * C::KCPR * 16, V_LDS_CLASS = C::NW * RV * C::VCPR * 16;
+  constexpr int K_LDS_PASS = K_ROWS_PER_PASS * C::KCPR * 16, V_LDS_PASS = V_ROWS_PER_PASS * C::VCPR * 16;
+  const uint32_t ldsK_addr = (uint32_t)(uintptr_t)lds + wave * RK * (C::KCPR * 16);
+  const uint32_t ldsV_addr = (uint32_t)(uintptr_t)lds + KBUF * 16 + wave * RV * (C::VCPR * 16);
 
-  // Requests the K rows and V^T rows of step `half` of key block m into buffer `buf`.
-  auto issue_step = [&](int m, int half, int buf) {
+  const int nsteps = nlist * C::SPB;
+  // The list is read through the constant address space: a scalar load, which neither waits
+  // for nor is held up by the direct-to-LDS loads in flight (a vector load would be both).
+  typedef const int32_t __attribute__((address_space(4))) * const_list_t;
+  const const_list_t clist = (const_list_t)(uintptr_t)list;
+  auto block_of = [&](int s) __attribute__((always_inline)) {
+    const int j = s / C::SPB;
+    return list ? clist[j] : j;
+  };
+  // Request the K rows and the V^T rows of step s into ring stage `st`.
+  auto issue_step = [&](int s, int st) __attribute__((always_inline)) {
+    const int m = block_of(s), part = s % C::SPB;
     const int kv_count = dm.block_count(m);
     const uint16_t* kblk = Kb + dm.block_start(m) * dm.st;
-    const uint32_t kdst = ldsK_addr + buf * (KBUF * 16), vdst = ldsV_addr + buf * (VBUF * 16);
+    const uint32_t kdst = ldsK_addr + st * (C::STAGE * 16), vdst = ldsV_addr + st * (C::STAGE * 16);
     if (kv_count == BLK) {
-      const uint16_t* ksrc = kblk + (int64_t)(half * KVS) * dm.st;
 #pragma unroll
-      for (int ii = 0; ii < C::KPW; ++ii) dma16_sv(kdst + ii * 1024, ksrc, k_voff[ii], ldsK);
+      for (int ii = 0; ii < C::KPW; ++ii)
+        dma16_sv(kdst + (ii / KOFF) * K_LDS_PASS + (ii % KOFF) * K_LDS_CLASS,
+                 kblk + (int64_t)(part * KVS + (ii / KOFF) * K_ROWS_PER_PASS) * dm.st, k_voff[ii % KOFF], lds);
     } else {
 #pragma unroll
       for (int ii = 0; ii < C::KPW; ++ii) {
-        int r = half * KVS + k_row[ii];
+        int r = part * KVS + (ii / KOFF) * K_ROWS_PER_PASS + k_r0[ii % KOFF];
         r = r < kv_count ? r : kv_count - 1;   // rows past a ragged block re-read its last row (masked later)
-        dma16_v(kdst + ii * 1024, kblk + (int64_t)r * dm.st + k_col[ii], ldsK);
+        dma16_sv(kdst + (ii / KOFF) * K_LDS_PASS + (ii % KOFF) * K_LDS_CLASS, kblk,
+                 (uint32_t)((r * dm.st + k_col[ii % KOFF]) * 2), lds);
       }
     }
-    const uint16_t* vsrc = Vtb + (size_t)m * D * BLK + half * KVS;
+    const uint16_t* vsrc = Vtb + (size_t)m * D * BLK + part * KVS;
 #pragma unroll
-    for (int ii = 0; ii < C::VPW; ++ii) dma16_sv(vdst + ii * 1024, vsrc, v_voff[ii], ldsV);
+    for (int ii = 0; ii < C::VPW; ++ii)
+      dma16_sv(vdst + (ii / VOFF) * V_LDS_PASS + (ii % VOFF) * V_LDS_CLASS,
+               vsrc + (size_t)((ii / VOFF) * V_ROWS_PER_PASS) * BLK, v_voff[ii % VOFF], lds);
   };
+  constexpr int LPS = C::KPW + C::VPW;           // loads per step per wave
 
-  // ---- loop-invariant LDS read positions (16-byte chunk index inside buffer 0, tile 0) ----
+  // ---- loop-invariant LDS read positions (16-byte chunk index inside stage 0, tile 0) ----
   const u32x4* kread[C::KS];
   const u32x4* vread[C::PC];
 #pragma unroll
-  for (int ks = 0; ks < C::KS; ++ks) kread[ks] = ldsK + swizzled<C::KCPR>(l32, 2 * ks + hf);
+  for (int ks = 0; ks < C::KS; ++ks) kread[ks] = lds + swizzled<C::KCPR>(l32, 2 * ks + hf);
 #pragma unroll
-  for (int pc = 0; pc < C::PC; ++pc) vread[pc] = ldsV + swizzled<C::VCPR>(l32, 2 * pc + hf);
+  for (int pc = 0; pc < C::PC; ++pc) vread[pc] = lds + KBUF + swizzled<C::VCPR>(l32, 2 * pc + hf);
 
   // ---- Q as the B operand of S^T = K Q^T, resident in registers --------------------------
   const int q_count = dm.block_count(qb);
@@ -227,6 +251,10 @@ __global__ __launch_bounds__(64 * BLK / 32, (BLK == 128 ? 2 : 1)) void attn_kern
       if (q < q_count) v = *reinterpret_cast<const uint4*>(Qb + (q_t0 + q) * dm.st + 16 * s + 8 * hf);
       qreg[s] = __builtin_bit_cast(bf16x8, v);
     }
+    // Q must have arrived before the first direct-to-LDS load is requested: the compiler
+    // does not see those loads, and would otherwise place its own wait for Q -- a wait for
+    // *every* outstanding load -- at the first use inside the loop.
+    __builtin_amdgcn_s_waitcnt(0x0F70);
   }
 
   floatx16 oacc[C::DT];
@@ -237,42 +265,47 @@ __global__ __launch_bounds__(64 * BLK / 32, (BLK == 128 ? 2 : 1)) void attn_kern
   float mref = -INFINITY, lpart = 0.f;   // softmax reference (log2 domain) and this lane's partial row sum
   const float cs = dm.scale * kLog2e;
 
-  // One step: 64 keys of block m_cur from buffer BUF (compile-time, so every LDS offset is
-  // an immediate), after requesting the following step into the other buffer.
-  auto step = [&](auto bufc, int half, int m_cur, bool more, int m_next, int half_next) {
-    constexpr int BUF = decltype(bufc)::value;
-    const int kv_count = dm.block_count(m_cur);
-    wait_all_loads();      // this wave's share of the step has landed
-    __syncthreads();       // ... and everyone's; every wave is past the previous step, so the other buffer is free
-    if (more) issue_step(m_next, half_next, BUF ^ 1);
+  // One step: KVS keys from ring stage ST (compile time, so every LDS offset is an
+  // immediate), after requesting step s + NSTAGE - 1 into the stage the previous step freed.
+  auto step = [&](auto stc, int s) __attribute__((always_inline)) {
+    constexpr int ST = decltype(stc)::value;
+    // this wave's share of step s has landed: all but the loads of the newer steps in flight
+    if (s + NSTAGE - 2 < nsteps) wait_loads_leaving<(NSTAGE - 2) * LPS>(); else wait_loads_leaving<0>();
+    __syncthreads();       // ... and everyone's; every wave is past step s-1, whose stage is free now
+    if (s + NSTAGE - 1 < nsteps) issue_step(s + NSTAGE - 1, (ST + NSTAGE - 1) % NSTAGE);
+    const int kv_count = dm.block_count(block_of(s));
 
-    // ---- S^T = K Q^T: all K operands of the step are requested from LDS up front ---------
-    bf16x8 kop[C::KS][C::KT];
-#pragma unroll
-    for (int ks = 0; ks < C::KS; ++ks)
-#pragma unroll
-      for (int t = 0; t < C::KT; ++t)
-        kop[ks][t] = __builtin_bit_cast(bf16x8, kread[ks][BUF * KBUF + t * 32 * C::KCPR]);
-    __builtin_amdgcn_sched_barrier(0);
+    // ---- S^T = K Q^T -------------------------------------------------------------------
     floatx16 sacc[C::KT];
 #pragma unroll
     for (int t = 0; t < C::KT; ++t)
 #pragma unroll
       for (int r = 0; r < 16; ++r) sacc[t][r] = 0.f;
+    constexpr int KSP = C::KS / NSPLIT;
 #pragma unroll
-    for (int ks = 0; ks < C::KS; ++ks)
+    for (int h2 = 0; h2 < NSPLIT; ++h2) {
+      bf16x8 kop[KSP][C::KT];
 #pragma unroll
-      for (int t = 0; t < C::KT; ++t)
-        sacc[t] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(kop[ks][t], qreg[ks], sacc[t], 0, 0, 0);
-    __builtin_amdgcn_sched_barrier(0);
+      for (int k2 = 0; k2 < KSP; ++k2)
+#pragma unroll
+        for (int t = 0; t < C::KT; ++t)
+          kop[k2][t] = __builtin_bit_cast(bf16x8, kread[h2 * KSP + k2][ST * C::STAGE + t * 32 * C::KCPR]);
+#pragma unroll
+      for (int k2 = 0; k2 < KSP; ++k2)
+#pragma unroll
+        for (int t = 0; t < C::KT; ++t)
+          sacc[t] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(kop[k2][t], qreg[h2 * KSP + k2], sacc[t], 0, 0, 0);
+      __builtin_amdgcn_sched_barrier(0);
+    }
 
-    // accumulator register r of key tile t is key half*64 + 32t + 8(r/4) + 4*hf + r%4 of the block
+    // accumulator register r of key tile t is key part*KVS + 32t + 8(r/4) + 4*hf + r%4 of the block
     if (kv_count < BLK) {
+      const int part = s % C::SPB;
 #pragma unroll
       for (int t = 0; t < C::KT; ++t)
 #pragma unroll
         for (int r = 0; r < 16; ++r) {
-          const int kv = half * KVS + 32 * t + 8 * (r / 4) + 4 * hf + (r % 4);
+          const int kv = part * KVS + 32 * t + 8 * (r / 4) + 4 * hf + (r % 4);
           if (kv >= kv_count) sacc[t][r] = -INFINITY;
         }
     }
@@ -294,8 +327,8 @@ __global__ __launch_bounds__(64 * BLK / 32, (BLK == 128 ? 2 : 1)) void attn_kern
 #pragma unroll
         for (int r = 0; r < 16; ++r) oacc[dt][r] *= alpha;
     }
-    const float moff = -mref;
-    u32x4 pb[C::PC];   // probabilities as bf16 B operands, 16 keys per entry
+    const float moff = -mref;   // finite: the first step of a list always holds a valid key
+    u32x4 pb[C::PC];            // probabilities as bf16 B operands, 16 keys per entry
     float rs = 0.f;
 #pragma unroll
     for (int t = 0; t < C::KT; ++t) {
@@ -318,48 +351,40 @@ __global__ __launch_bounds__(64 * BLK / 32, (BLK == 128 ? 2 : 1)) void attn_kern
     lpart += rs;
     __builtin_amdgcn_sched_barrier(0);
 
-    // ---- O^T += V^T P^T: all V operands requested up front ---------------------------------
-    bf16x8 vop[C::PC][C::DT];
+    // ---- O^T += V^T P^T ----------------------------------------------------------------
+    constexpr int PCP = C::PC / NSPLIT;
 #pragma unroll
-    for (int pc = 0; pc < C::PC; ++pc)
+    for (int h2 = 0; h2 < NSPLIT; ++h2) {
+      bf16x8 vop[PCP][C::DT];
 #pragma unroll
-      for (int dt = 0; dt < C::DT; ++dt)
-        vop[pc][dt] = __builtin_bit_cast(bf16x8, vread[pc][BUF * VBUF + dt * 32 * C::VCPR]);
-    __builtin_amdgcn_sched_barrier(0);
+      for (int p2 = 0; p2 < PCP; ++p2)
 #pragma unroll
-    for (int pc = 0; pc < C::PC; ++pc)
+        for (int dt = 0; dt < C::DT; ++dt)
+          vop[p2][dt] = __builtin_bit_cast(bf16x8, vread[h2 * PCP + p2][ST * C::STAGE + dt * 32 * C::VCPR]);
 #pragma unroll
-      for (int dt = 0; dt < C::DT; ++dt)
-        oacc[dt] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(vop[pc][dt], __builtin_bit_cast(bf16x8, pb[pc]), oacc[dt], 0, 0, 0);
+      for (int p2 = 0; p2 < PCP; ++p2)
+#pragma unroll
+        for (int dt = 0; dt < C::DT; ++dt)
+          oacc[dt] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(vop[p2][dt], __builtin_bit_cast(bf16x8, pb[h2 * PCP + p2]),
+                                                             oacc[dt], 0, 0, 0);
+      __builtin_amdgcn_sched_barrier(0);
+    }
   };
 
-  // Steps alternate between the two buffers; with two steps per key block the buffer index
-  // is the half index, with one step per block the blocks alternate.
-  if (nlist > 0) {
-    int m_cur = list ? list[0] : 0;
-    issue_step(m_cur, 0, 0);
-    if constexpr (C::SPB == 2) {
-      for (int j = 0; j < nlist; ++j) {
-        const bool more = j + 1 < nlist;
-        const int m_next = more ? (list ? list[j + 1] : j + 1) : m_cur;
-        step(IntC<0>{}, 0, m_cur, true, m_cur, 1);
-        step(IntC<1>{}, 1, m_cur, more, m_next, 0);
-        m_cur = m_next;
-      }
-    } else {
-      for (int j = 0; j < nlist; j += 2) {
-        const bool more1 = j + 1 < nlist, more2 = j + 2 < nlist;
-        const int m1 = more1 ? (list ? list[j + 1] : j + 1) : m_cur;
-        const int m2 = more2 ? (list ? list[j + 2] : j + 2) : m1;
-        step(IntC<0>{}, 0, m_cur, more1, m1, 0);
-        if (more1) step(IntC<1>{}, 0, m1, more2, m2, 0);
-        m_cur = m2;
-      }
-    }
+  // prologue: the first NSTAGE-1 steps are requested; then the ring turns one stage per step
+#pragma unroll
+  for (int p = 0; p < NSTAGE - 1; ++p)
+    if (p < nsteps) issue_step(p, p);
+  for (int s = 0; s < nsteps; s += NSTAGE) {
+    step(IntC<0>{}, s);
+    if constexpr (NSTAGE > 1) { if (s + 1 < nsteps) step(IntC<1 % NSTAGE>{}, s + 1); }
+    if constexpr (NSTAGE > 2) { if (s + 2 < nsteps) step(IntC<2 % NSTAGE>{}, s + 2); }
+    if constexpr (NSTAGE > 3) { if (s + 3 < nsteps) step(IntC<3 % NSTAGE>{}, s + 3); }
+    static_assert(NSTAGE <= 4, "unroll the ring loop further for deeper rings");
   }
 
   // ---- epilogue: normalise, rectify, compensate, store ------------------------------------
-  __syncthreads();   // comp[] is complete
+  const bool do_comp = sparse_row && (a.flags & RSA_COMPENSATE);
   const float rfac = (sparse_row && (a.flags & RSA_RECTIFY_CRITICAL)) ? a.R[vrow] : 1.0f;
   uint16_t* Ob = a.O + base;
   {
@@ -368,6 +393,7 @@ __global__ __launch_bounds__(64 * BLK / 32, (BLK == 128 ? 2 : 1)) void attn_kern
     if (q < q_count) {
       const float f = rfac / lsum;
       uint16_t* orow = Ob + (q_t0 + q) * dm.st;
+      const float* crow = a.comp + vrow * D;     // C_n of this query block (only read when do_comp)
 #pragma unroll
       for (int dt = 0; dt < C::DT; ++dt)
 #pragma unroll
@@ -375,9 +401,11 @@ __global__ __launch_bounds__(64 * BLK / 32, (BLK == 128 ? 2 : 1)) void attn_kern
           const int d0 = 32 * dt + 8 * g + 4 * hf;
           float o[4];
 #pragma unroll
-          for (int e = 0; e < 4; ++e) {
-            o[e] = oacc[dt][4 * g + e] * f;
-            if (do_comp) o[e] += comp[0][d0 + e] + comp[1][d0 + e];
+          for (int e = 0; e < 4; ++e) o[e] = oacc[dt][4 * g + e] * f;
+          if (do_comp) {
+            const floatx4 c4 = *reinterpret_cast<const floatx4*>(crow + d0);
+#pragma unroll
+            for (int e = 0; e < 4; ++e) o[e] += c4[e];
           }
           uint2 w;
           w.x = pack_bf16x2(o[0], o[1]);
@@ -390,6 +418,57 @@ __global__ __launch_bounds__(64 * BLK / 32, (BLK == 128 ? 2 : 1)) void attn_kern
   }
 }
 
+// Pooled compensation (Alg. 1 step 21): C[n][:] = sum over blocks m that are not kept and
+// have their M_c bit set of A^pool[n][m] * v^pool[m][:], fp32. Eight query blocks per
+// workgroup share every staged chunk of 32 pooled value rows.
+template <int D>
+__global__ __launch_bounds__(256) void compensation_kernel(Dims dm, AttnArgs a) {
+  constexpr int NQ = 8, MC = 32;
+  __shared__ float vtile[MC][D];
+  __shared__ float wt[NQ][MC];
+  const int bh = blockIdx.y, n0 = blockIdx.x * NQ;
+  const int tid = threadIdx.x;
+  const int dd = tid % D;
+  constexpr int NPT = NQ * D / 256;            // query blocks per thread
+  const int nq0 = (tid / D) * NPT;
+  float acc[NPT];
+#pragma unroll
+  for (int i = 0; i < NPT; ++i) acc[i] = 0.f;
+  const float* Vp = a.Vp + (size_t)bh * dm.m * D;
+  for (int wd = 0; wd < dm.w; ++wd) {
+    const int m0 = wd * 32;
+    // weights of this 32-block chunk for the NQ rows (zero where not compensated)
+    {
+      const int r = tid / MC, j = tid % MC;   // 256 threads = NQ x MC
+      float wv = 0.f;
+      const int n = n0 + r, m = m0 + j;
+      if (n < dm.n && m < dm.m) {
+        const size_t row = (size_t)bh * dm.n + n;
+        const uint32_t bits = ~a.mask_bits[row * dm.w + wd] & a.Mc_bits[row * dm.w + wd];
+        if ((bits >> j) & 1u) wv = a.Apool[row * dm.m + m];
+      }
+      wt[r][j] = wv;
+    }
+    for (int idx = tid; idx < MC * D; idx += 256) {
+      const int j = idx / D, c = idx % D;
+      vtile[j][c] = (m0 + j < dm.m) ? Vp[(size_t)(m0 + j) * D + c] : 0.f;
+    }
+    __syncthreads();
+#pragma unroll 8
+    for (int j = 0; j < MC; ++j) {
+      const float v = vtile[j][dd];
+#pragma unroll
+      for (int i = 0; i < NPT; ++i) acc[i] = fmaf(wt[nq0 + i][j], v, acc[i]);
+    }
+    __syncthreads();
+  }
+#pragma unroll
+  for (int i = 0; i < NPT; ++i) {
+    const int n = n0 + nq0 + i;
+    if (n < dm.n) a.comp[((size_t)bh * dm.n + n) * D + dd] = acc[i];
+  }
+}
+
 template <int D, int BLK>
 hipError_t launch_attn_t(const Dims& dm, const AttnArgs& a, hipStream_t s) {
   using C = AttnCfg<D, BLK>;
@@ -399,6 +478,8 @@ hipError_t launch_attn_t(const Dims& dm, const AttnArgs& a, hipStream_t s) {
   const int chunk = (dm.n + 7) / 8;
   const long long grid = (long long)n_text_items + (dense_all ? 0 : (long long)bh * 8 * chunk);
   if (grid <= 0 || grid > 0x7fffffffLL) return hipErrorInvalidValue;
+  if (!dense_all && (a.flags & RSA_COMPENSATE))
+    hipLaunchKernelGGL((compensation_kernel<D>), dim3((dm.n + 7) / 8, bh), dim3(256), 0, s, dm, a);
   hipLaunchKernelGGL((attn_kernel<D, BLK>), dim3((unsigned)grid), dim3(C::NTHR), 0, s, dm, a, n_text_items, chunk);
   return hipGetLastError();
 }

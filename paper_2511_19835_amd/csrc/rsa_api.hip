@@ -57,6 +57,11 @@ PoolWs pool_ws_layout(const Dims& d) {
   return w;
 }
 
+// rsa_sparse_attn_rectified scratch: the pooled compensation term C_n, fp32 [b][h][N][d].
+size_t attn_ws_size(const Dims& d) {
+  return align256((size_t)d.batch * d.heads * d.n * d.d * sizeof(float));
+}
+
 }  // namespace
 
 extern "C" {
@@ -77,7 +82,7 @@ int rsa_workspace_bytes(const rsa_shape* shape, size_t* pool_ws_bytes, size_t* a
   int rc = make_dims(shape, &d);
   if (rc != RSA_OK) return rc;
   if (pool_ws_bytes) *pool_ws_bytes = pool_ws_layout(d).total;
-  if (attn_ws_bytes) *attn_ws_bytes = 0;
+  if (attn_ws_bytes) *attn_ws_bytes = attn_ws_size(d);
   return RSA_OK;
 }
 
@@ -142,7 +147,6 @@ int rsa_sparse_attn_rectified(const rsa_shape* shape, const void* Q, const void*
                               const uint32_t* mask_bits, const float* R, const float* Apool,
                               const uint32_t* Mc_bits, const float* Vp, int flags, void* O,
                               float* lse, void* ws, size_t ws_bytes, void* stream) {
-  (void)ws; (void)ws_bytes;
   Dims d;
   int rc = make_dims(shape, &d);
   if (rc != RSA_OK) return rc;
@@ -154,11 +158,15 @@ int rsa_sparse_attn_rectified(const rsa_shape* shape, const void* Q, const void*
     if (!block_idx || !count) return RSA_E_NULL;
     if ((flags & RSA_RECTIFY_CRITICAL) && !R) return RSA_E_NULL;
     if ((flags & RSA_COMPENSATE) && (!mask_bits || !Apool || !Mc_bits || !Vp)) return RSA_E_NULL;
+    if (flags & RSA_COMPENSATE) {
+      if (!ws) return RSA_E_NULL;
+      if (ws_bytes < attn_ws_size(d) || ((uintptr_t)ws & 255)) return RSA_E_WORKSPACE;
+    }
   }
   rsa::AttnArgs aa;
   aa.Q = (const uint16_t*)Q; aa.K = (const uint16_t*)K; aa.Vt = (const uint16_t*)Vt;
   aa.block_idx = block_idx; aa.count = count; aa.mask_bits = mask_bits; aa.Mc_bits = Mc_bits;
-  aa.R = R; aa.Apool = Apool; aa.Vp = Vp; aa.O = (uint16_t*)O; aa.lse = lse; aa.flags = flags;
+  aa.R = R; aa.Apool = Apool; aa.Vp = Vp; aa.O = (uint16_t*)O; aa.lse = lse; aa.comp = (float*)ws; aa.flags = flags;
   if (rsa::launch_attn(d, aa, (hipStream_t)stream) != hipSuccess) return RSA_E_LAUNCH;
   return RSA_OK;
 }

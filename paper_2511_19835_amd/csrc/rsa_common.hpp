@@ -89,6 +89,7 @@ struct AttnArgs {
   const float *R, *Apool, *Vp;
   uint16_t* O;
   float* lse;
+  float* comp;             // workspace [b][h][N][d]: pooled compensation term C_n
   int flags;
 };
 hipError_t launch_attn(const Dims& dm, const AttnArgs& a, hipStream_t s);

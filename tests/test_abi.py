@@ -40,6 +40,7 @@ def test_block_counts_and_workspace(lib):
     assert (n, m, w) == (929, 931, 30)
     pool_ws, attn_ws = rb.rsa_workspace_bytes(_shape())
     assert pool_ws > 0 and pool_ws % 256 == 0
+    assert attn_ws == 1 * 2 * 8 * 128 * 4
 
 
 @pytest.mark.parametrize("kw,code", [
@@ -67,6 +68,10 @@ def test_null_and_range_arguments_are_rejected_before_launch(lib):
     att = lambda flags, q=one, lists=one: lib.rsa_sparse_attn_rectified(
         ctypes.byref(sh), q, one, one, lists, lists, one, one, one, one, one, flags, one, None, None, 0, None)
     assert att(8) == -5 and att(3, None) == -1 and att(3, one, None) == -1
+    # RSA_COMPENSATE needs the C_n workspace: present, large enough, 256-byte aligned
+    attw = lambda flags, ws, nbytes: lib.rsa_sparse_attn_rectified(
+        ctypes.byref(sh), one, one, one, one, one, one, one, one, one, one, flags, one, None, ws, nbytes, None)
+    assert attw(3, None, 0) == -1 and attw(2, one, 16) == -4 and attw(2, ctypes.c_void_p(8), 1 << 30) == -4
     assert lib.rsa_status_string(-4).decode().startswith("workspace")
     assert lib.rsa_status_string(0).decode() == "ok"
 
