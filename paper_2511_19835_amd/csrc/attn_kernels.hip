@@ -131,7 +131,7 @@ template <int D, int BLK>
 __global__ __launch_bounds__(64 * BLK / 32, (BLK == 128 ? 2 : 1)) void attn_kernel(Dims dm, AttnArgs a, int n_text_items,
                                                                                   int chunk) {
   using C = AttnCfg<D, BLK>;
-  constexpr int KBUF = C::KBUF, VBUF = C::VBUF;
+  constexpr int KBUF = C::KBUF;
   __shared__ u32x4 lds[NSTAGE * C::STAGE];      // ring: stage st = [K rows | V^T rows]
 
   // ---- which (batch*head, query block) is this workgroup ---------------------------------
@@ -419,52 +419,60 @@ __global__ __launch_bounds__(64 * BLK / 32, (BLK == 128 ? 2 : 1)) void attn_kern
 }
 
 // Pooled compensation (Alg. 1 step 21): C[n][:] = sum over blocks m that are not kept and
-// have their M_c bit set of A^pool[n][m] * v^pool[m][:], fp32. Eight query blocks per
-// workgroup share every staged chunk of 32 pooled value rows.
+// have their M_c bit set of A^pool[n][m] * v^pool[m][:], all fp32. A workgroup owns NQ = 16
+// query blocks and walks the key blocks in chunks of 512: first the chunk's weights
+// (A^pool where the block is compensated, else 0) go to LDS as one float4 per (group of four
+// query blocks, key block); then every thread accumulates one channel of 16*D/256 query
+// blocks, reading the weights as LDS broadcasts and v^pool straight from global memory
+// (coalesced, L2 resident, independent loads the compiler keeps in flight).
+constexpr int kCompNQ = 16, kCompMCH = 512;
+
 template <int D>
 __global__ __launch_bounds__(256) void compensation_kernel(Dims dm, AttnArgs a) {
-  constexpr int NQ = 8, MC = 32;
-  __shared__ float vtile[MC][D];
-  __shared__ float wt[NQ][MC];
+  constexpr int NQ = kCompNQ, MCH = kCompMCH, NG = NQ / 4;
+  constexpr int RPT = NQ * D / 256;            // query blocks per thread (a multiple of 4)
+  __shared__ floatx4 wt4[NG * MCH];
   const int bh = blockIdx.y, n0 = blockIdx.x * NQ;
   const int tid = threadIdx.x;
-  const int dd = tid % D;
-  constexpr int NPT = NQ * D / 256;            // query blocks per thread
-  const int nq0 = (tid / D) * NPT;
-  float acc[NPT];
+  const int dd = tid % D, g0 = (tid / D) * (RPT / 4);       // first weight group of this thread
+  float acc[RPT];
 #pragma unroll
-  for (int i = 0; i < NPT; ++i) acc[i] = 0.f;
-  const float* Vp = a.Vp + (size_t)bh * dm.m * D;
-  for (int wd = 0; wd < dm.w; ++wd) {
-    const int m0 = wd * 32;
-    // weights of this 32-block chunk for the NQ rows (zero where not compensated)
-    {
-      const int r = tid / MC, j = tid % MC;   // 256 threads = NQ x MC
-      float wv = 0.f;
-      const int n = n0 + r, m = m0 + j;
-      if (n < dm.n && m < dm.m) {
-        const size_t row = (size_t)bh * dm.n + n;
-        const uint32_t bits = ~a.mask_bits[row * dm.w + wd] & a.Mc_bits[row * dm.w + wd];
-        if ((bits >> j) & 1u) wv = a.Apool[row * dm.m + m];
+  for (int i = 0; i < RPT; ++i) acc[i] = 0.f;
+  const float* Vp = a.Vp + (size_t)bh * dm.m * D + dd;
+  for (int m0 = 0; m0 < dm.m; m0 += MCH) {
+    const int mc = dm.m - m0 < MCH ? dm.m - m0 : MCH;
+    for (int idx = tid; idx < NG * MCH; idx += 256) {
+      const int g = idx / MCH, mm = idx % MCH, m = m0 + mm;
+      floatx4 w = {0.f, 0.f, 0.f, 0.f};
+      if (mm < mc) {
+#pragma unroll
+        for (int e = 0; e < 4; ++e) {
+          const int n = n0 + 4 * g + e;
+          if (n < dm.n) {
+            const size_t row = (size_t)bh * dm.n + n;
+            const uint32_t bits = ~a.mask_bits[row * dm.w + m / 32] & a.Mc_bits[row * dm.w + m / 32];
+            if ((bits >> (m % 32)) & 1u) w[e] = a.Apool[row * dm.m + m];
+          }
+        }
       }
-      wt[r][j] = wv;
-    }
-    for (int idx = tid; idx < MC * D; idx += 256) {
-      const int j = idx / D, c = idx % D;
-      vtile[j][c] = (m0 + j < dm.m) ? Vp[(size_t)(m0 + j) * D + c] : 0.f;
+      wt4[idx] = w;
     }
     __syncthreads();
 #pragma unroll 8
-    for (int j = 0; j < MC; ++j) {
-      const float v = vtile[j][dd];
+    for (int mm = 0; mm < mc; ++mm) {
+      const float v = Vp[(size_t)(m0 + mm) * D];
 #pragma unroll
-      for (int i = 0; i < NPT; ++i) acc[i] = fmaf(wt[nq0 + i][j], v, acc[i]);
+      for (int q = 0; q < RPT / 4; ++q) {
+        const floatx4 w = wt4[(g0 + q) * MCH + mm];
+#pragma unroll
+        for (int e = 0; e < 4; ++e) acc[4 * q + e] = fmaf(w[e], v, acc[4 * q + e]);
+      }
     }
     __syncthreads();
   }
 #pragma unroll
-  for (int i = 0; i < NPT; ++i) {
-    const int n = n0 + nq0 + i;
+  for (int i = 0; i < RPT; ++i) {
+    const int n = n0 + 4 * g0 + i;
     if (n < dm.n) a.comp[((size_t)bh * dm.n + n) * D + dd] = acc[i];
   }
 }
@@ -479,7 +487,7 @@ hipError_t launch_attn_t(const Dims& dm, const AttnArgs& a, hipStream_t s) {
   const long long grid = (long long)n_text_items + (dense_all ? 0 : (long long)bh * 8 * chunk);
   if (grid <= 0 || grid > 0x7fffffffLL) return hipErrorInvalidValue;
   if (!dense_all && (a.flags & RSA_COMPENSATE))
-    hipLaunchKernelGGL((compensation_kernel<D>), dim3((dm.n + 7) / 8, bh), dim3(256), 0, s, dm, a);
+    hipLaunchKernelGGL((compensation_kernel<D>), dim3((dm.n + kCompNQ - 1) / kCompNQ, bh), dim3(256), 0, s, dm, a);
   hipLaunchKernelGGL((attn_kernel<D, BLK>), dim3((unsigned)grid), dim3(C::NTHR), 0, s, dm, a, n_text_items, chunk);
   return hipGetLastError();
 }

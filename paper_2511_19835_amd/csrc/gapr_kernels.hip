@@ -10,24 +10,34 @@
 // (gain and error both divided by c_n c_m). Each deviation is a skinny GEMM of a token
 // block against all pooled vectors of the other side, so the cost is tokens x blocks x d.
 //
-// deviation_kernel: one workgroup per token block; every wave keeps the whole block as the
-// MFMA A operand in registers and walks the pooled vectors 32 at a time. The pooled
-// operand is rounded to bf16; accumulation is fp32. The block mean of the products is
-// taken from the same accumulators, so the subtraction gives (x_i - mean_i x_i) . p_bf16
-// exactly up to fp32 rounding and the only approximation left is p_bf16 for p: a relative
-// error of ~1e-3 per product with random sign, ~1e-4 after the mean over the block's rows,
-// an order of magnitude inside the band in which the gate is allowed to differ.
+// deviation_kernel: one workgroup per token block. The block is read once, centred on its
+// pooled vector (x_i - x^pool, fp32 subtraction, rounded to bf16) and parked in LDS; every
+// wave then keeps the whole centred block as the MFMA A operand in registers and walks the
+// pooled vectors of the other side 32 at a time, so the accumulators hold the deviations
+// themselves and the epilogue is one |.|-add per element. The pooled operand is rounded to
+// bf16 as well; accumulation is fp32. Both roundings perturb a product by ~2^-9 relative
+// with random sign: a few 1e-4 relative on DA / DB after the mean over the block's rows,
+// inside the band in which the gate is allowed to differ from fp64 arithmetic.
 #include "rsa_common.hpp"
 
 namespace rsa {
 namespace {
 
+typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));
+
+// 16-byte chunk c of row r sits at chunk position c ^ key(r): 16 consecutive rows read at one
+// logical chunk index then touch every LDS bank once. CPR = chunks per row (8 or 16).
+template <int CPR>
+__device__ __forceinline__ int swizzled(int r, int c) { return r * CPR + (c ^ ((r / (16 / CPR)) & (CPR - 1))); }
+
 template <int D, int BLK>
 __global__ __launch_bounds__(256, 2) void deviation_kernel(Dims dm, const uint16_t* __restrict__ X,
-                                                           int n_blocks_x,
+                                                           const float* __restrict__ Xpool, int n_blocks_x,
                                                            const uint16_t* __restrict__ PB,
                                                            int n_other, float* __restrict__ out) {
-  constexpr int MT = BLK / 32, KS = D / 16;
+  constexpr int MT = BLK / 32, KS = D / 16, CPR = D / 8;
+  constexpr int RPP = 256 / CPR;                 // rows staged per pass of the workgroup
+  __shared__ u32x4 atile[BLK * CPR];
   const int xb = blockIdx.x, bh = blockIdx.y;
   const int b = bh / dm.heads, h = bh % dm.heads;
   const int wave = threadIdx.x / 64, lane = threadIdx.x % 64;
@@ -36,56 +46,91 @@ __global__ __launch_bounds__(256, 2) void deviation_kernel(Dims dm, const uint16
   const int64_t t0 = dm.block_start(xb);
   const uint16_t* Xb = X + (int64_t)b * dm.sb + (int64_t)h * dm.sh;
 
-  bf16x8 areg[MT][KS];
+  // ---- stage the centred block: thread -> chunk column tid % CPR, rows tid / CPR + RPP*i ----
+  {
+    const int cc = threadIdx.x % CPR, r0 = threadIdx.x / CPR;
+    const float* mp = Xpool + ((size_t)bh * n_blocks_x + xb) * D + 8 * cc;
+    const floatx4 m0 = *reinterpret_cast<const floatx4*>(mp);
+    const floatx4 m1 = *reinterpret_cast<const floatx4*>(mp + 4);
+    u32x4 raw[BLK / RPP];
 #pragma unroll
-  for (int t = 0; t < MT; ++t) {
-    const int row = 32 * t + l32;
+    for (int i = 0; i < BLK / RPP; ++i) {
+      const int r = r0 + RPP * i;
+      const int rr = r < count ? r : count - 1;                  // stay inside the tensor; zeroed below
+      raw[i] = *reinterpret_cast<const u32x4*>(Xb + (t0 + rr) * dm.st + 8 * cc);
+    }
 #pragma unroll
-    for (int s = 0; s < KS; ++s) {
-      uint4 v = make_uint4(0, 0, 0, 0);
-      if (row < count) v = *reinterpret_cast<const uint4*>(Xb + (t0 + row) * dm.st + 16 * s + 8 * hf);
-      areg[t][s] = __builtin_bit_cast(bf16x8, v);
+    for (int i = 0; i < BLK / RPP; ++i) {
+      const int r = r0 + RPP * i;
+      u32x4 c;
+      c.x = pack_bf16x2(bf16_bits_to_float(raw[i].x & 0xffffu) - m0[0], bf16_bits_to_float(raw[i].x >> 16) - m0[1]);
+      c.y = pack_bf16x2(bf16_bits_to_float(raw[i].y & 0xffffu) - m0[2], bf16_bits_to_float(raw[i].y >> 16) - m0[3]);
+      c.z = pack_bf16x2(bf16_bits_to_float(raw[i].z & 0xffffu) - m1[0], bf16_bits_to_float(raw[i].z >> 16) - m1[1]);
+      c.w = pack_bf16x2(bf16_bits_to_float(raw[i].w & 0xffffu) - m1[2], bf16_bits_to_float(raw[i].w >> 16) - m1[3]);
+      if (r >= count) c = u32x4{0u, 0u, 0u, 0u};                // rows past a ragged block contribute nothing
+      atile[swizzled<CPR>(r, cc)] = c;
     }
   }
-  const float inv_c = 1.0f / (float)count;
-  float* orow = out + ((size_t)bh * n_blocks_x + xb) * n_other;
+  __syncthreads();
+  bf16x8 areg[MT][KS];
+#pragma unroll
+  for (int t = 0; t < MT; ++t)
+#pragma unroll
+    for (int s = 0; s < KS; ++s) areg[t][s] = __builtin_bit_cast(bf16x8, atile[swizzled<CPR>(32 * t + l32, 2 * s + hf)]);
 
-  for (int o0 = 32 * wave; o0 < n_other; o0 += 128) {
+  const float outscale = dm.scale / (float)count;
+  float* orow = out + ((size_t)bh * n_blocks_x + xb) * n_other;
+  const uint16_t* PBh = PB + (size_t)bh * n_other * D + 8 * hf;
+
+  // The B operand of one iteration is 32 pooled vectors: lane (l32, hf) supplies channels
+  // 16s + 8hf .. +7 of vector o0 + l32 for k-step s. The first half of the k-steps is fetched
+  // one iteration ahead, the second half at the top of the iteration, behind the MFMAs of
+  // the first half.
+  constexpr int KH = KS / 2;
+  auto vec_ptr = [&](int o0) __attribute__((always_inline)) {
     const int o = o0 + l32;
-    const bool ovalid = o < n_other;
-    const uint16_t* prow = PB + ((size_t)bh * n_other + (ovalid ? o : 0)) * D + 8 * hf;
+    return PBh + (size_t)(o < n_other ? o : n_other - 1) * D;    // clamped: columns past the end are not stored
+  };
+  u32x4 bpre[KH], bcur[KH];
+  {
+    const uint16_t* p = vec_ptr(32 * wave);
+#pragma unroll
+    for (int s = 0; s < KH; ++s) bpre[s] = *reinterpret_cast<const u32x4*>(p + 16 * s);
+  }
+  for (int o0 = 32 * wave; o0 < n_other; o0 += 128) {
+    const uint16_t* p = vec_ptr(o0);
+#pragma unroll
+    for (int s = 0; s < KH; ++s) bcur[s] = *reinterpret_cast<const u32x4*>(p + 16 * (KH + s));
     floatx16 acc[MT];
 #pragma unroll
     for (int t = 0; t < MT; ++t)
 #pragma unroll
       for (int r = 0; r < 16; ++r) acc[t][r] = 0.f;
 #pragma unroll
-    for (int s = 0; s < KS; ++s) {
-      uint4 vb = make_uint4(0, 0, 0, 0);
-      if (ovalid) vb = *reinterpret_cast<const uint4*>(prow + 16 * s);
-      const bf16x8 bop = __builtin_bit_cast(bf16x8, vb);
+    for (int s = 0; s < KH; ++s)
 #pragma unroll
       for (int t = 0; t < MT; ++t)
-        acc[t] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(areg[t][s], bop, acc[t], 0, 0, 0);
+        acc[t] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(areg[t][s], __builtin_bit_cast(bf16x8, bpre[s]), acc[t], 0, 0, 0);
+    __builtin_amdgcn_sched_barrier(0);
+    if (o0 + 128 < n_other) {
+      const uint16_t* pn = vec_ptr(o0 + 128);
+#pragma unroll
+      for (int s = 0; s < KH; ++s) bpre[s] = *reinterpret_cast<const u32x4*>(pn + 16 * s);
     }
-    // accumulator register r of tile t holds row 32t + 8(r/4) + 4*hf + r%4, column l32
-    float cs = 0.f;
 #pragma unroll
-    for (int t = 0; t < MT; ++t)
+    for (int s = 0; s < KH; ++s)
 #pragma unroll
-      for (int r = 0; r < 16; ++r) cs += acc[t][r];   // rows past the block end are exact zeros
-    cs += __shfl_xor(cs, 32);
-    const float mean = cs * inv_c;
+      for (int t = 0; t < MT; ++t)
+        acc[t] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(areg[t][KH + s], __builtin_bit_cast(bf16x8, bcur[s]), acc[t], 0, 0, 0);
+    // every accumulator of a lane belongs to column o0 + l32; its rows are spread over the
+    // registers and the two half-waves
     float dv = 0.f;
 #pragma unroll
     for (int t = 0; t < MT; ++t)
 #pragma unroll
-      for (int r = 0; r < 16; ++r) {
-        const int row = 32 * t + 8 * (r / 4) + 4 * hf + (r % 4);
-        dv += (row < count) ? fabsf(acc[t][r] - mean) : 0.f;
-      }
+      for (int r = 0; r < 16; ++r) dv += fabsf(acc[t][r]);
     dv += __shfl_xor(dv, 32);
-    if (hf == 0 && ovalid) orow[o] = dv * inv_c * dm.scale;
+    if (hf == 0 && o0 + l32 < n_other) orow[o0 + l32] = dv * outscale;
   }
 }
 
@@ -135,8 +180,8 @@ __global__ void fill_bits_kernel(Dims dm, uint32_t* bits, uint32_t value) {
 template <int D, int BLK>
 hipError_t launch_gapr_t(const Dims& dm, const GaprArgs& a, hipStream_t s) {
   const int bh = dm.batch * dm.heads;
-  hipLaunchKernelGGL((deviation_kernel<D, BLK>), dim3(dm.n, bh), dim3(256), 0, s, dm, a.Q, dm.n, a.Kpb, dm.m, a.DA);
-  hipLaunchKernelGGL((deviation_kernel<D, BLK>), dim3(dm.m, bh), dim3(256), 0, s, dm, a.K, dm.m, a.Qpb, dm.n, a.DBt);
+  hipLaunchKernelGGL((deviation_kernel<D, BLK>), dim3(dm.n, bh), dim3(256), 0, s, dm, a.Q, a.Qp, dm.n, a.Kpb, dm.m, a.DA);
+  hipLaunchKernelGGL((deviation_kernel<D, BLK>), dim3(dm.m, bh), dim3(256), 0, s, dm, a.K, a.Kp, dm.m, a.Qpb, dm.n, a.DBt);
   hipLaunchKernelGGL(gate_kernel, dim3(dm.w, (dm.n + 31) / 32, bh), dim3(256), 0, s, dm, a);
   return hipGetLastError();
 }

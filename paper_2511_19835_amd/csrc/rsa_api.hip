@@ -115,6 +115,7 @@ int rsa_pool(const rsa_shape* shape, const void* Q, const void* K, const void* V
 
   rsa::GaprArgs ga;
   ga.Q = (const uint16_t*)Q; ga.K = (const uint16_t*)K;
+  ga.Qp = Qp; ga.Kp = Kp;
   ga.Qpb = pa.Qpb; ga.Kpb = pa.Kpb; ga.Spool = Spool;
   ga.DA = (float*)(wsb + wl.da); ga.DBt = (float*)(wsb + wl.dbt);
   ga.Mc_bits = Mc_bits; ga.mode = gapr_mode;

@@ -63,6 +63,7 @@ hipError_t launch_scores(const Dims& dm, const ScoreArgs& a, hipStream_t s);
 
 struct GaprArgs {
   const uint16_t *Q, *K;
+  const float *Qp, *Kp;    // fp32 pooled vectors (the centre of each token block)
   const uint16_t *Qpb, *Kpb;
   const float* Spool;
   float *DA, *DBt;         // [b][h][N][M], [b][h][M][N]
