@@ -38,6 +38,13 @@ the reading taken is stated at the function; the list of readings is:
       represented by its directly pooled key.
   R8  V^pool covers all M blocks (Alg. 1 step 3 pools V, step 21 multiplies an N x M
       matrix with it).
+  R9  M_adja (Alg. 1 "Require", step 14; Sec. 4.3 "retaining spatial-temporal neighbor
+      blocks") is not defined further in the paper. Reading: the video latent grid is cut
+      into tiles (the tiles of the token order); a video query block and a video key block
+      are neighbours when some token of one and some token of the other lie in tiles whose
+      tile coordinates differ by at most `radius` (default 1) along every axis -- the
+      block itself and, where blocks and tiles coincide, its 26 surrounding tiles. Text
+      key blocks are never forced by it.
 
 Parity pins live in tests/test_oracle_*.py. Unpinned (needs the paper's models): the
 appendix statistic on softmax denominators, every quality table and alignment figure.
@@ -51,7 +58,7 @@ import numpy as np
 
 __all__ = [
     "bf16_bits_to_f64", "Partition", "partition", "pool", "pooled_scores", "ipar",
-    "kept_count", "select_blocks", "rectification_factor", "gapr", "gapr_signed_sums",
+    "kept_count", "select_blocks", "adjacency_mask", "rectification_factor", "gapr", "gapr_signed_sums",
     "sparse_attention_block", "sparse_attention", "dense_attention", "compensation", "rectified_layer_head",
     "rectified_layer",
 ]
@@ -158,6 +165,23 @@ def select_blocks(A_pool: np.ndarray, sparsity: float, p: float = 0.0,
         mask[n, order[:keep]] = True
     if forced is not None:
         mask |= np.asarray(forced, dtype=bool)
+    return mask
+
+
+def adjacency_mask(coords: np.ndarray, tile, part: Partition, radius: int = 1) -> np.ndarray:
+    """M_adja (Alg. 1 step 14; Sec. 4.3; reading R9) as a boolean [N, M] mask.
+
+    coords [T_v, 3]: the (t, h, w) latent-grid coordinate of every video token in the order
+    the tokens are stored; tile = (tile_t, tile_h, tile_w). Columns of text blocks are False.
+    """
+    N, M = part.n_video, part.n_blocks
+    tile_of = np.asarray(coords, dtype=np.int64) // np.asarray(tile, dtype=np.int64)[None, :]
+    tiles = [np.unique(tile_of[part.tokens(n)], axis=0) for n in range(N)]     # tiles block n touches
+    mask = np.zeros((N, M), dtype=bool)
+    for n in range(N):
+        for m in range(N):
+            d = np.abs(tiles[n][:, None, :] - tiles[m][None, :, :]).max(axis=2)    # Chebyshev distances
+            mask[n, m] = bool((d <= radius).any())
     return mask
 
 

@@ -29,7 +29,7 @@ from typing import Iterable, Optional, Tuple
 import numpy as np
 
 __all__ = [
-    "LayerConfig", "CONFIGS", "tile_order_coords", "make_head", "make_inputs",
+    "LayerConfig", "CONFIGS", "default_tile", "tile_order_coords", "make_head", "make_inputs",
     "f32_to_bf16_bits", "bf16_bits_to_f32", "sha256_of",
 ]
 
@@ -94,9 +94,16 @@ def bf16_bits_to_f32(b: np.ndarray) -> np.ndarray:
     return (np.ascontiguousarray(b, dtype=np.uint16).astype(np.uint32) << np.uint32(16)).view(np.float32)
 
 
-def tile_order_coords(grid: Tuple[int, int, int], block: int) -> np.ndarray:
+def default_tile(block: int) -> Tuple[int, int, int]:
+    """Tile of the token order used for a block size: 64 tokens = (1, 8, 8), 128 = (2, 8, 8)."""
+    return (1, 8, 8) if block <= 64 else (2, 8, 8)
+
+
+def tile_order_coords(grid: Tuple[int, int, int], block: int,
+                      tile: Optional[Tuple[int, int, int]] = None) -> np.ndarray:
     """(t, h, w) coordinate of every video token in tile order, shape [T*H*W, 3]."""
-    tile = (1, 8, 8) if block <= 64 else (2, 8, 8)
+    if tile is None:
+        tile = default_tile(block)
     T, H, W = grid
     out = []
     for t0 in range(0, T, tile[0]):
