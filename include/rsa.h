@@ -125,6 +125,22 @@ int rsa_select_blocks(const rsa_shape* shape, const float* Lmass, const float* A
                       void* stream);
 
 /*
+ * Alg. 1 "Require" and step 14, Sec. 4.3 (spatial-temporal neighbour blocks are always kept):
+ * the adjacency mask M_adja for a video latent grid whose tokens are stored tile by tile
+ * (tiles in raster order over (T, H, W), tokens in raster order inside a tile, partial tiles
+ * at the upper faces of the grid). A video query block n and a video key block m are
+ * neighbours when some tile touched by n and some tile touched by m differ by at most
+ * `radius` in every tile coordinate (radius 1: the block itself and the surrounding 26 tiles
+ * where blocks and tiles coincide). Text key blocks are never set.
+ *   grid [3], tile [3]   HOST arrays (T, H, W) and (tile_t, tile_h, tile_w); T*H*W must equal
+ *                        t_video (RSA_E_SHAPE otherwise); radius in [0, 64]
+ *   forced_bits          device, [b][h][N][W] u32, fully overwritten (same rows for every b, h);
+ *                        pass it to rsa_select_blocks
+ */
+int rsa_adjacency_mask(const rsa_shape* shape, const int32_t* grid, const int32_t* tile, int radius,
+                       uint32_t* forced_bits, void* stream);
+
+/*
  * Alg. 1 steps 16-23. For video query block n: online-softmax attention of its tokens over
  * the tokens of the blocks in block_idx[n][0..count[n]) only (masked keys are excluded from
  * the softmax, Sec. 3.1), times R[n] (RSA_RECTIFY_CRITICAL), plus

@@ -23,6 +23,7 @@ SOURCES = [
     "score_kernels.hip",
     "gapr_kernels.hip",
     "select_kernels.hip",
+    "adjacency_kernels.hip",
     "attn_kernels.hip",
 ]
 

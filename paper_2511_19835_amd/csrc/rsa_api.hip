@@ -143,6 +143,20 @@ int rsa_select_blocks(const rsa_shape* shape, const float* Lmass, const float* A
   return RSA_OK;
 }
 
+int rsa_adjacency_mask(const rsa_shape* shape, const int32_t* grid, const int32_t* tile, int radius,
+                       uint32_t* forced_bits, void* stream) {
+  Dims d;
+  int rc = make_dims(shape, &d);
+  if (rc != RSA_OK) return rc;
+  if (!grid || !tile || !forced_bits) return RSA_E_NULL;
+  for (int i = 0; i < 3; ++i)
+    if (grid[i] < 1 || tile[i] < 1) return RSA_E_SHAPE;
+  if ((int64_t)grid[0] * grid[1] * grid[2] != d.tv) return RSA_E_SHAPE;
+  if (radius < 0 || radius > 64) return RSA_E_RANGE;
+  if (rsa::launch_adjacency(d, grid, tile, radius, forced_bits, (hipStream_t)stream) != hipSuccess) return RSA_E_LAUNCH;
+  return RSA_OK;
+}
+
 int rsa_sparse_attn_rectified(const rsa_shape* shape, const void* Q, const void* K, const void* Vt,
                               const int32_t* block_idx, const int32_t* count,
                               const uint32_t* mask_bits, const float* R, const float* Apool,

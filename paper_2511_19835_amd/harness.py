@@ -75,3 +75,18 @@ def run_layer(Q_bits: np.ndarray, K_bits: np.ndarray, V_bits: np.ndarray, t_vide
         O_bits=device_to_bits(O), lse=lse.cpu().numpy() if lse is not None else None,
     )
     return out
+
+
+def adjacency_mask(t_video: int, t_text: int, block: int, head_dim: int, grid, tile, radius: int = 1,
+                   batch: int = 1, heads: int = 1, device="cuda:0") -> np.ndarray:
+    """rsa_adjacency_mask on the GPU, brought back as a boolean [batch, heads, N, M] array."""
+    t = t_video + t_text
+    shape = rb.rsa_shape(batch=batch, heads=heads, head_dim=head_dim, block=block, t_video=t_video, t_text=t_text,
+                         stride_b=heads * t * head_dim, stride_h=t * head_dim, stride_t=head_dim, scale=0.0)
+    n, m, w = rb.rsa_block_counts(shape)
+    bits = torch.full((batch, heads, n, w), -1, dtype=torch.int32, device=device)   # must be fully overwritten
+    rb.rsa_adjacency_mask(shape, grid, tile, radius, bits)
+    torch.cuda.synchronize()
+    words = bits.cpu().numpy().view(np.uint32)
+    assert (words[..., -1] >> np.uint32((m - 1) % 32 + 1) == 0).all() or m % 32 == 0, "bits past M must be clear"
+    return unpack_bits(words, m)

@@ -72,6 +72,12 @@ def test_null_and_range_arguments_are_rejected_before_launch(lib):
     attw = lambda flags, ws, nbytes: lib.rsa_sparse_attn_rectified(
         ctypes.byref(sh), one, one, one, one, one, one, one, one, one, one, flags, one, None, ws, nbytes, None)
     assert attw(3, None, 0) == -1 and attw(2, one, 16) == -4 and attw(2, ctypes.c_void_p(8), 1 << 30) == -4
+    # adjacency mask: grid must multiply out to t_video, tile entries positive, radius in range
+    i3 = lambda *v: (ctypes.c_int32 * 3)(*v)
+    adj = lambda grid, tile, radius, out=one: lib.rsa_adjacency_mask(ctypes.byref(sh), grid, tile, radius, out, None)
+    assert adj(i3(10, 10, 10), i3(2, 8, 8), 1, None) == -1 and adj(None, i3(2, 8, 8), 1) == -1
+    assert adj(i3(10, 10, 11), i3(2, 8, 8), 1) == -2 and adj(i3(10, 10, 10), i3(2, 0, 8), 1) == -2
+    assert adj(i3(10, 10, 10), i3(2, 8, 8), -1) == -5 and adj(i3(10, 10, 10), i3(2, 8, 8), 65) == -5
     assert lib.rsa_status_string(-4).decode().startswith("workspace")
     assert lib.rsa_status_string(0).decode() == "ok"
 

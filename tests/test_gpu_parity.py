@@ -237,3 +237,35 @@ def test_full_size_hunyuan_shape_sampled(gpu):
                                  query_blocks=blocks)
         st = parity.compare_head(out, 0, h, ref, Qb[0, h], Kb[0, h], Vb[0, h], query_blocks=blocks)
         print(f"  [hunyuan h{h}] {st}", flush=True)
+
+
+@pytest.mark.parametrize("grid,tile,block,t_text,radius", [
+    ((4, 16, 16), (1, 8, 8), 64, 64, 1),        # tiny: blocks coincide with tiles
+    ((13, 30, 52), (2, 8, 8), 128, 0, 1),       # mid: partial tiles along every axis
+    ((5, 9, 17), (1, 8, 8), 64, 30, 1),         # one-token-wide partial tiles, ragged last block
+    ((5, 9, 17), (2, 4, 4), 128, 0, 2),
+    ((3, 20, 20), (2, 8, 8), 64, 0, 0),         # radius 0: blocks that share a tile
+    ((33, 45, 80), (2, 8, 8), 128, 256, 1),     # the benchmark shape
+])
+def test_adjacency_mask_is_bit_exact(gpu, grid, tile, block, t_text, radius):
+    """rsa_adjacency_mask against the oracle's tile-set definition, every bit, every (b, h)."""
+    from oracle import rsa_oracle as ro
+    tv = grid[0] * grid[1] * grid[2]
+    got = gpu.adjacency_mask(tv, t_text, block, 64, grid, tile, radius, batch=1, heads=2)
+    coords = synth.tile_order_coords(grid, block, tile)
+    part = ro.partition(tv, t_text, block)
+    ref = ro.adjacency_mask(coords, tile, part, radius)
+    assert got.shape == (1, 2) + ref.shape
+    assert np.array_equal(got[0, 0], ref) and np.array_equal(got[0, 1], ref)
+
+
+def test_full_mask_rule_mid(gpu):
+    """Alg. 1 steps 13-14 as the paper runs them: top-k, weight threshold p = 0.3 (appendix,
+    parameter table) and the adjacency mask generated on the GPU, 2 heads of the mid config."""
+    cfg = synth.CONFIGS["mid"]
+    adja = gpu.adjacency_mask(cfg.t_video, cfg.t_text, cfg.block, cfg.head_dim, cfg.grid,
+                              synth.default_tile(cfg.block), 1, batch=1, heads=2)
+    out, stats, _ = _run_and_compare(gpu, cfg, heads=[0, 5], p=0.3, forced=adja)
+    k = 159 - int(np.floor(0.9 * 159 + 1e-6))
+    assert (out["count"] >= k).all() and (out["count"] > k).any()          # rows have different lengths now
+    assert (out["mask"][:, :, :, :] >= adja).all()                         # every neighbour is kept
