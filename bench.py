@@ -28,7 +28,7 @@ PEAK_BF16_MFMA_TFLOPS = 2500.0     # MI355X dense bf16 MFMA
 PEAK_HBM_GBS = 8000.0              # MI355X HBM3E
 
 
-def cpu_baseline(cfg, sparsity, Qb, Kb, Vb, gpu_O_bits, gpu_mask, gpu_Mc, budget_s=15.0):
+def cpu_baseline(cfg, sparsity, Qb, Kb, Vb, gpu_O_bits, gpu_mask, gpu_Mc, budget_s=15.0, p_thr=0.0, full_rule=False):
     """Time the oracle, as it stands, on the host cores for a bounded sample of the same
     workload (head 0: pooled stages in full, then query blocks in a seeded random order
     until the time budget is used), and compare the GPU output on exactly those blocks.
@@ -47,7 +47,11 @@ def cpu_baseline(cfg, sparsity, Qb, Kb, Vb, gpu_O_bits, gpu_mask, gpu_Mc, budget
     Qp, Kp, Vp = ro.pool(Q, part), ro.pool(K, part), ro.pool(V, part)
     A_pool = ro.ipar(Qp[:N], Kp[:N], K[cfg.t_video:], part, scale)
     Mc, G, E = ro.gapr(Q, K, Qp, Kp, part, scale, 1)
-    mask = ro.select_blocks(A_pool, sparsity)
+    forced = None
+    if full_rule:
+        tile = synth.default_tile(cfg.block)
+        forced = ro.adjacency_mask(synth.tile_order_coords(cfg.grid, cfg.block, tile), tile, part, 1)
+    mask = ro.select_blocks(A_pool, sparsity, p_thr, forced)
     R = ro.rectification_factor(A_pool, mask)
     C = ro.compensation(A_pool, mask, Mc, Vp)
     t_pooled = time.perf_counter() - t0
@@ -115,6 +119,8 @@ MEASURED_TRAFFIC_BYTES = {("hunyuan", 0.9, 0, 24): 50.39e6 * 2.0 * 1024 + 716.6e
 
 
 def measured_traffic(cfg, sparsity, args):
+    if args.mask_rule != "topk":
+        return None
     return MEASURED_TRAFFIC_BYTES.get((cfg.name, round(float(sparsity), 6), args.seed, cfg.heads))
 
 
@@ -127,6 +133,9 @@ def main():
     ap.add_argument("--sparsity", type=float, default=None)
     ap.add_argument("--seed", type=int, default=0)
     ap.add_argument("--heads", type=int, default=None, help="override the head count (smaller runs)")
+    ap.add_argument("--mask-rule", choices=("topk", "full"), default="topk",
+                    help="topk: the k largest blocks per row (the configuration the metric is quoted on); "
+                         "full: top-k, weight threshold p = 0.3 and the adjacency mask (paper's parameter table)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-dense", action="store_true")
     ap.add_argument("--dense-steps", type=int, default=1)
@@ -159,6 +168,11 @@ def main():
     O = torch.empty_like(Q)
     buf = rb.allocate(Q, cfg.t_video, cfg.t_text, cfg.block)
     flags = rb.RSA_RECTIFY_CRITICAL | rb.RSA_COMPENSATE
+    p_thr, forced = 0.0, None
+    if args.mask_rule == "full":
+        p_thr = 0.3
+        forced = torch.empty_like(buf.mask_bits)
+        rb.rsa_adjacency_mask(buf.shape, cfg.grid, synth.default_tile(cfg.block), 1, forced)   # geometry only: once
 
     def step(events=None):
         if events is not None:
@@ -167,7 +181,7 @@ def main():
                     buf.Mc_bits, 1, buf.pool_ws)
         if events is not None:
             events[1].record()
-        rb.rsa_select_blocks(buf.shape, buf.Lmass, buf.Apool, sparsity, 0.0, None, buf.mask_bits, buf.block_idx,
+        rb.rsa_select_blocks(buf.shape, buf.Lmass, buf.Apool, sparsity, p_thr, forced, buf.mask_bits, buf.block_idx,
                              buf.count, buf.R)
         if events is not None:
             events[2].record()
@@ -214,7 +228,8 @@ def main():
                         f"{cfg.grid[0]}x{cfg.grid[1]}x{cfg.grid[2]} = {cfg.t_video} video + {cfg.t_text} text tokens, "
                         f"block {Bk}, sparsity {sparsity:g}, seed {args.seed}",
             "kept_blocks_per_video_row": int(counts.flat[0]), "key_blocks": M,
-            "realised_sparsity": realised_sparsity, "gapr_mode": 1, "p": 0.0,
+            "realised_sparsity": realised_sparsity, "gapr_mode": 1, "p": p_thr,
+            "mask_rule": args.mask_rule, "kept_blocks_min_mean_max": [int(counts.min()), float(counts.mean()), int(counts.max())],
         },
         "stages_ms": {"rsa_pool": pool_ms, "rsa_select_blocks": select_ms, "rsa_sparse_attn_rectified": attn_ms},
         "roofline": {
@@ -266,7 +281,8 @@ def main():
         O_head0 = harness.device_to_bits(O[0, 0])
         gmask = harness.unpack_bits(buf.mask_bits[0, 0].cpu().numpy(), M)
         gmc = harness.unpack_bits(buf.Mc_bits[0, 0].cpu().numpy(), M)
-        base, par, ref = cpu_baseline(cfg, sparsity, Qb[0, 0], Kb[0, 0], Vb[0, 0], O_head0, gmask, gmc)
+        base, par, ref = cpu_baseline(cfg, sparsity, Qb[0, 0], Kb[0, 0], Vb[0, 0], O_head0, gmask, gmc,
+                                      p_thr=p_thr, full_rule=args.mask_rule == "full")
         out["cpu_baseline"] = base
         out["parity_sample"] = par
     print(json.dumps(out))
