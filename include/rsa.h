@@ -125,6 +125,20 @@ int rsa_select_blocks(const rsa_shape* shape, const float* Lmass, const float* A
                       void* stream);
 
 /*
+ * Appendix "Implementations" (the token sequence is reordered before inference so that blocks
+ * hold spatially close tokens): moves the rows of one [b][h][T][d] bf16 tensor between raster
+ * order (token index (t*H + h)*W + w) and the tile order the other entry points expect (tiles of
+ * `tile` in raster order over the (T, H, W) grid, tokens in raster order inside a tile). Text
+ * rows [t_video, T) keep their place.
+ *   direction 0: dst[tile-order position] = src[raster index]   (before the layer: Q, K, V)
+ *   direction 1: dst[raster index] = src[tile-order position]   (after the layer: O)
+ *   grid [3], tile [3]: HOST arrays; T*H*W must equal t_video. src and dst: device, both with the
+ *   strides of `shape`, must not alias (RSA_E_RANGE). dst is fully overwritten.
+ */
+int rsa_reorder_tokens(const rsa_shape* shape, const int32_t* grid, const int32_t* tile, int direction,
+                       const void* src, void* dst, void* stream);
+
+/*
  * Alg. 1 "Require" and step 14, Sec. 4.3 (spatial-temporal neighbour blocks are always kept):
  * the adjacency mask M_adja for a video latent grid whose tokens are stored tile by tile
  * (tiles in raster order over (T, H, W), tokens in raster order inside a tile, partial tiles

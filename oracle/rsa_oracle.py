@@ -58,7 +58,7 @@ import numpy as np
 
 __all__ = [
     "bf16_bits_to_f64", "Partition", "partition", "pool", "pooled_scores", "ipar",
-    "kept_count", "select_blocks", "adjacency_mask", "rectification_factor", "gapr", "gapr_signed_sums",
+    "kept_count", "select_blocks", "tile_order", "reorder_tokens", "adjacency_mask", "rectification_factor", "gapr", "gapr_signed_sums",
     "sparse_attention_block", "sparse_attention", "dense_attention", "compensation", "rectified_layer_head",
     "rectified_layer",
 ]
@@ -166,6 +166,37 @@ def select_blocks(A_pool: np.ndarray, sparsity: float, p: float = 0.0,
     if forced is not None:
         mask |= np.asarray(forced, dtype=bool)
     return mask
+
+
+def tile_order(grid, tile) -> np.ndarray:
+    """Raster index (t*H + h)*W + w of the video token stored at every position of the tile
+    order (appendix "Implementations": tokens are reordered so that a block holds spatially
+    close tokens; the order used here cuts the (T, H, W) grid into tiles, walks the tiles in
+    raster order and the tokens of a tile in raster order). Returns int64 [T*H*W]."""
+    T, H, W = (int(x) for x in grid)
+    tt, th, tw = (int(x) for x in tile)
+    order = []
+    for t0 in range(0, T, tt):
+        for h0 in range(0, H, th):
+            for w0 in range(0, W, tw):
+                for t in range(t0, min(t0 + tt, T)):
+                    for h in range(h0, min(h0 + th, H)):
+                        for w in range(w0, min(w0 + tw, W)):
+                            order.append((t * H + h) * W + w)
+    return np.asarray(order, dtype=np.int64)
+
+
+def reorder_tokens(X: np.ndarray, grid, tile, direction: int) -> np.ndarray:
+    """Rows of X [T, d] moved between raster order and tile order; text rows (beyond T*H*W)
+    keep their place. direction 0: raster -> tile order; 1: tile order -> raster."""
+    order = tile_order(grid, tile)
+    tv = order.size
+    Y = np.array(X, copy=True)
+    if direction == 0:
+        Y[:tv] = X[order]
+    else:
+        Y[order] = X[:tv]
+    return Y
 
 
 def adjacency_mask(coords: np.ndarray, tile, part: Partition, radius: int = 1) -> np.ndarray:

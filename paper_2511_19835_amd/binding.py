@@ -23,7 +23,7 @@ RSA_DENSE = 4
 RSA_MAX_BLOCKS = 4096
 
 EXPORTS = (
-    "rsa_block_counts", "rsa_workspace_bytes", "rsa_pool", "rsa_adjacency_mask", "rsa_select_blocks",
+    "rsa_block_counts", "rsa_workspace_bytes", "rsa_pool", "rsa_adjacency_mask", "rsa_reorder_tokens", "rsa_select_blocks",
     "rsa_sparse_attn_rectified", "rsa_status_string",
 )
 
@@ -71,6 +71,8 @@ def _lib() -> ctypes.CDLL:
         lib.rsa_sparse_attn_rectified.restype = ctypes.c_int
         lib.rsa_adjacency_mask.argtypes = [shp, ctypes.POINTER(ctypes.c_int32), ctypes.POINTER(ctypes.c_int32), ctypes.c_int, vp, vp]
         lib.rsa_adjacency_mask.restype = ctypes.c_int
+        lib.rsa_reorder_tokens.argtypes = [shp, ctypes.POINTER(ctypes.c_int32), ctypes.POINTER(ctypes.c_int32), ctypes.c_int, vp, vp, vp]
+        lib.rsa_reorder_tokens.restype = ctypes.c_int
         lib.rsa_status_string.argtypes = [ctypes.c_int]
         lib.rsa_status_string.restype = ctypes.c_char_p
         _LIB = lib
@@ -138,6 +140,13 @@ def rsa_adjacency_mask(shape, grid, tile, radius, forced_bits, stream=None):
     t = (ctypes.c_int32 * 3)(*[int(x) for x in tile])
     _check(_lib().rsa_adjacency_mask(ctypes.byref(shape), g, t, int(radius), _ptr(forced_bits), _stream_ptr(stream)),
            "rsa_adjacency_mask")
+
+
+def rsa_reorder_tokens(shape, grid, tile, direction, src, dst, stream=None):
+    g = (ctypes.c_int32 * 3)(*[int(x) for x in grid])
+    t = (ctypes.c_int32 * 3)(*[int(x) for x in tile])
+    _check(_lib().rsa_reorder_tokens(ctypes.byref(shape), g, t, int(direction), _ptr(src), _ptr(dst),
+                                     _stream_ptr(stream)), "rsa_reorder_tokens")
 
 
 def rsa_sparse_attn_rectified(shape, Q, K, Vt, block_idx, count, mask_bits, R, Apool, Mc_bits, Vp, flags, O,

@@ -24,6 +24,7 @@ SOURCES = [
     "gapr_kernels.hip",
     "select_kernels.hip",
     "adjacency_kernels.hip",
+    "reorder_kernels.hip",
     "attn_kernels.hip",
 ]
 

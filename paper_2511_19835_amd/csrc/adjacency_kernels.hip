@@ -14,41 +14,10 @@
 // integer divisions. One thread decides one (query block, key block) pair; a ballot packs 32
 // decisions into a mask word, written for every (batch, head).
 #include "rsa_common.hpp"
+#include "tile_geom.hpp"
 
 namespace rsa {
 namespace {
-
-struct TileGeom {
-  int T, H, W;        // latent grid
-  int tt, th, tw;     // tile
-  int nb, nc;         // tiles along h and w
-  int radius;
-};
-
-struct TileIdx { int a, b, c; };
-
-__device__ inline TileIdx tile_of_token(const TileGeom& g, int x) {
-  TileIdx t;
-  const int layer = g.tt * g.H * g.W;                 // tokens of a full layer of tiles
-  t.a = x / layer;
-  const int ct = min(g.tt, g.T - t.a * g.tt);
-  int rem = x - t.a * layer;
-  const int strip = ct * g.th * g.W;                  // tokens of a full strip of tiles along w
-  t.b = rem / strip;
-  const int ch = min(g.th, g.H - t.b * g.th);
-  rem -= t.b * strip;
-  t.c = rem / (ct * ch * g.tw);
-  return t;
-}
-__device__ inline int raster(const TileGeom& g, TileIdx t) { return (t.a * g.nb + t.b) * g.nc + t.c; }
-__device__ inline TileIdx unraster(const TileGeom& g, int r) {
-  TileIdx t;
-  t.c = r % g.nc;
-  r /= g.nc;
-  t.b = r % g.nb;
-  t.a = r / g.nb;
-  return t;
-}
 
 __global__ __launch_bounds__(64) void adjacency_kernel(Dims dm, TileGeom g, uint32_t* __restrict__ bits) {
   const int n = blockIdx.y;
@@ -86,12 +55,7 @@ __global__ __launch_bounds__(64) void adjacency_kernel(Dims dm, TileGeom g, uint
 
 hipError_t launch_adjacency(const Dims& dm, const int* grid, const int* tile, int radius, uint32_t* bits,
                             hipStream_t s) {
-  TileGeom g;
-  g.T = grid[0]; g.H = grid[1]; g.W = grid[2];
-  g.tt = tile[0]; g.th = tile[1]; g.tw = tile[2];
-  g.nb = (g.H + g.th - 1) / g.th;
-  g.nc = (g.W + g.tw - 1) / g.tw;
-  g.radius = radius;
+  const TileGeom g = make_tile_geom(grid, tile, radius);
   hipLaunchKernelGGL(adjacency_kernel, dim3((dm.w + 1) / 2, dm.n), dim3(64), 0, s, dm, g, bits);
   return hipGetLastError();
 }

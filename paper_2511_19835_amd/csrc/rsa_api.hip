@@ -157,6 +157,22 @@ int rsa_adjacency_mask(const rsa_shape* shape, const int32_t* grid, const int32_
   return RSA_OK;
 }
 
+int rsa_reorder_tokens(const rsa_shape* shape, const int32_t* grid, const int32_t* tile, int direction,
+                       const void* src, void* dst, void* stream) {
+  Dims d;
+  int rc = make_dims(shape, &d);
+  if (rc != RSA_OK) return rc;
+  if (!grid || !tile || !src || !dst) return RSA_E_NULL;
+  for (int i = 0; i < 3; ++i)
+    if (grid[i] < 1 || tile[i] < 1) return RSA_E_SHAPE;
+  if ((int64_t)grid[0] * grid[1] * grid[2] != d.tv) return RSA_E_SHAPE;
+  if ((direction != 0 && direction != 1) || src == dst) return RSA_E_RANGE;
+  if (rsa::launch_reorder(d, grid, tile, direction, (const uint16_t*)src, (uint16_t*)dst, (hipStream_t)stream) !=
+      hipSuccess)
+    return RSA_E_LAUNCH;
+  return RSA_OK;
+}
+
 int rsa_sparse_attn_rectified(const rsa_shape* shape, const void* Q, const void* K, const void* Vt,
                               const int32_t* block_idx, const int32_t* count,
                               const uint32_t* mask_bits, const float* R, const float* Apool,

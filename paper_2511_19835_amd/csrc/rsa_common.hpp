@@ -86,6 +86,9 @@ hipError_t launch_select(const Dims& dm, const SelectArgs& a, hipStream_t s);
 hipError_t launch_adjacency(const Dims& dm, const int* grid, const int* tile, int radius, uint32_t* bits,
                             hipStream_t s);
 
+hipError_t launch_reorder(const Dims& dm, const int* grid, const int* tile, int direction, const uint16_t* src,
+                          uint16_t* dst, hipStream_t s);
+
 struct AttnArgs {
   const uint16_t *Q, *K, *Vt;
   const int32_t *block_idx, *count;

@@ -90,3 +90,14 @@ def adjacency_mask(t_video: int, t_text: int, block: int, head_dim: int, grid, t
     words = bits.cpu().numpy().view(np.uint32)
     assert (words[..., -1] >> np.uint32((m - 1) % 32 + 1) == 0).all() or m % 32 == 0, "bits past M must be clear"
     return unpack_bits(words, m)
+
+
+def reorder_tokens(X_bits: np.ndarray, t_video: int, t_text: int, block: int, grid, tile, direction: int,
+                   layout: str = "bhtd", device="cuda:0") -> np.ndarray:
+    """rsa_reorder_tokens on the GPU for a [B, H, T, d] tensor of bf16 bit patterns."""
+    X = bits_to_device(X_bits, device, layout)
+    Y = torch.full_like(X, float("nan"))                      # every row must be overwritten
+    shape = rb.make_shape(X, t_video, t_text, block)
+    rb.rsa_reorder_tokens(shape, grid, tile, direction, X, Y)
+    torch.cuda.synchronize()
+    return device_to_bits(Y)

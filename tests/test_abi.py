@@ -78,6 +78,10 @@ def test_null_and_range_arguments_are_rejected_before_launch(lib):
     assert adj(i3(10, 10, 10), i3(2, 8, 8), 1, None) == -1 and adj(None, i3(2, 8, 8), 1) == -1
     assert adj(i3(10, 10, 11), i3(2, 8, 8), 1) == -2 and adj(i3(10, 10, 10), i3(2, 0, 8), 1) == -2
     assert adj(i3(10, 10, 10), i3(2, 8, 8), -1) == -5 and adj(i3(10, 10, 10), i3(2, 8, 8), 65) == -5
+    reo = lambda grid, direction, src=one, dst=ctypes.c_void_p(512): lib.rsa_reorder_tokens(
+        ctypes.byref(sh), grid, i3(2, 8, 8), direction, src, dst, None)
+    assert reo(i3(10, 10, 10), 0, None) == -1 and reo(i3(10, 10, 11), 0) == -2
+    assert reo(i3(10, 10, 10), 2) == -5 and reo(i3(10, 10, 10), 0, one, one) == -5
     assert lib.rsa_status_string(-4).decode().startswith("workspace")
     assert lib.rsa_status_string(0).decode() == "ok"
 

@@ -269,3 +269,24 @@ def test_full_mask_rule_mid(gpu):
     k = 159 - int(np.floor(0.9 * 159 + 1e-6))
     assert (out["count"] >= k).all() and (out["count"] > k).any()          # rows have different lengths now
     assert (out["mask"][:, :, :, :] >= adja).all()                         # every neighbour is kept
+
+
+@pytest.mark.parametrize("grid,tile,block,t_text,d,layout", [
+    ((4, 16, 16), (1, 8, 8), 64, 64, 64, "bhtd"),
+    ((5, 9, 17), (2, 8, 8), 128, 30, 128, "bthd"),
+    ((3, 5, 7), (2, 2, 4), 64, 0, 64, "bhtd"),
+    ((33, 45, 80), (2, 8, 8), 128, 256, 128, "bhtd"),
+])
+def test_reorder_tokens_is_bit_exact(gpu, grid, tile, block, t_text, d, layout):
+    """rsa_reorder_tokens against the oracle's enumeration of the tile order, both directions."""
+    from oracle import rsa_oracle as ro
+    tv = grid[0] * grid[1] * grid[2]
+    rng = np.random.default_rng(11)
+    X = rng.integers(0, 1 << 16, size=(1, 2, tv + t_text, d), dtype=np.uint16)
+    fwd = gpu.reorder_tokens(X, tv, t_text, block, grid, tile, 0, layout)
+    for h in range(2):
+        assert np.array_equal(fwd[0, h], ro.reorder_tokens(X[0, h], grid, tile, 0))
+    back = gpu.reorder_tokens(fwd, tv, t_text, block, grid, tile, 1, layout)
+    assert np.array_equal(back, X)
+    inv = gpu.reorder_tokens(X, tv, t_text, block, grid, tile, 1, layout)
+    assert np.array_equal(inv[0, 1], ro.reorder_tokens(X[0, 1], grid, tile, 1))

@@ -75,3 +75,29 @@ def test_forced_mask_only_adds_blocks_and_counts_toward_the_factor():
     assert np.array_equal(full, base | adja)
     R0, R1 = ro.rectification_factor(A_pool, base), ro.rectification_factor(A_pool, full)
     np.testing.assert_allclose(R1 - R0, (A_pool * (adja & ~base)).sum(axis=1), rtol=0, atol=1e-15)
+
+
+@pytest.mark.parametrize("grid,tile", [((3, 5, 7), (2, 2, 4)), ((4, 16, 16), (1, 8, 8)), ((5, 9, 17), (2, 8, 8))])
+def test_tile_order_is_a_bijection_that_agrees_with_the_input_generator(grid, tile):
+    order = ro.tile_order(grid, tile)
+    tv = grid[0] * grid[1] * grid[2]
+    assert sorted(order.tolist()) == list(range(tv))
+    # the coordinates the synthetic inputs are drawn on are laid out in the same order
+    coords = synth.tile_order_coords(grid, 64, tile)
+    assert np.array_equal(order, (coords[:, 0] * grid[1] + coords[:, 1]) * grid[2] + coords[:, 2])
+    # tokens of one tile are consecutive: along the order the tile index never decreases
+    tile_id = ((coords[:, 0] // tile[0]) * 1000 + coords[:, 1] // tile[1]) * 1000 + coords[:, 2] // tile[2]
+    assert (np.diff(tile_id) >= 0).all()
+
+
+def test_reorder_round_trip_and_text_rows_stay():
+    rng = np.random.default_rng(5)
+    grid, tile = (3, 5, 7), (2, 2, 4)
+    tv, tt = 105, 9
+    X = rng.normal(size=(tv + tt, 4))
+    Y = ro.reorder_tokens(X, grid, tile, 0)
+    assert np.array_equal(Y[tv:], X[tv:]) and not np.array_equal(Y[:tv], X[:tv])
+    assert np.array_equal(ro.reorder_tokens(Y, grid, tile, 1), X)
+    # first tile of the order: t in {0,1}, h in {0,1}, w in {0..3}, raster inside the tile
+    first = [(t * 5 + h) * 7 + w for t in range(2) for h in range(2) for w in range(4)]
+    assert np.array_equal(Y[:16], X[first])
