@@ -250,6 +250,30 @@ def main():
         "input_generation_s": round(t_gen, 1),
     }
 
+    # token reordering around the layer (not part of a step: inputs of a step are already in tile order)
+    if cfg.grid is not None:
+        tile = synth.default_tile(cfg.block)
+        tmp = torch.empty_like(Q)
+        rb.rsa_reorder_tokens(buf.shape, cfg.grid, tile, 0, Q, tmp)           # warm
+        torch.cuda.synchronize()
+        e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        reps = 5
+        e0.record()
+        for _ in range(reps):
+            rb.rsa_reorder_tokens(buf.shape, cfg.grid, tile, 0, Q, tmp)
+            rb.rsa_reorder_tokens(buf.shape, cfg.grid, tile, 1, tmp, O)
+        e1.record()
+        torch.cuda.synchronize()
+        ms = e0.elapsed_time(e1) / (2 * reps)
+        nbytes = 2.0 * H * T * d * 2                                            # one read + one write of a tensor
+        out["roofline_reorder"] = {"kernel": "reorder_kernel (rsa_reorder_tokens), one tensor", "bound": "hbm",
+                                   "achieved": nbytes / (ms * 1e-3) / 1e9, "peak": PEAK_HBM_GBS, "unit": "GB/s",
+                                   "frac": nbytes / (ms * 1e-3) / 1e9 / PEAK_HBM_GBS, "bytes": nbytes, "ms": ms,
+                                   "round_trip_identical": bool(torch.equal(O, Q))}
+        del tmp
+        step()                                                                  # restore the rectified output in O
+        torch.cuda.synchronize()
+
     if args.copy_calibration:
         src = Q.view(torch.int16)
         dst = torch.empty_like(src)

@@ -13,19 +13,41 @@
 namespace rsa {
 namespace {
 
+// A wave owns 64 consecutive positions: lane L works out where position p0 + L lives in raster
+// order (the integer divisions are done once per row, not once per 16-byte chunk), then the
+// wave moves the 64 rows 64/cpr at a time, fetching each row's source from the lane that
+// computed it. All cpr loads of a lane are independent and in flight together.
+template <int CPR>
 __global__ __launch_bounds__(256) void reorder_kernel(Dims dm, TileGeom g, int direction,
                                                       const uint16_t* __restrict__ src, uint16_t* __restrict__ dst) {
-  const int cpr = dm.d / 8;                                   // 16-byte chunks per row
-  const int64_t chunks = dm.t * cpr;
+  constexpr int RPI = 64 / CPR;                               // rows per load instruction of a wave
+  const int lane = threadIdx.x % 64;
   const int bh = blockIdx.y;
   const int64_t base = (int64_t)(bh / dm.heads) * dm.sb + (int64_t)(bh % dm.heads) * dm.sh;
-  for (int64_t i = blockIdx.x * (int64_t)blockDim.x + threadIdx.x; i < chunks; i += (int64_t)gridDim.x * blockDim.x) {
-    const int64_t pos = i / cpr;                              // position in tile order (video) / token index (text)
-    const int c = (int)(i % cpr);
-    const int64_t ras = pos < dm.tv ? raster_token_of_position(g, (int)pos) : pos;
-    const int64_t from = direction == 0 ? ras : pos, to = direction == 0 ? pos : ras;
-    const uint4 v = *reinterpret_cast<const uint4*>(src + base + from * dm.st + 8 * c);
-    *reinterpret_cast<uint4*>(dst + base + to * dm.st + 8 * c) = v;
+  const int64_t waves = (int64_t)gridDim.x * (blockDim.x / 64);
+  const int c = lane % CPR, sub = lane / CPR;
+  for (int64_t p0 = (blockIdx.x * (int64_t)(blockDim.x / 64) + threadIdx.x / 64) * 64; p0 < dm.t; p0 += waves * 64) {
+    const int64_t pos = p0 + lane;
+    int ras = (int)pos;                                       // text rows and rows past the end: identity
+    if (pos < dm.tv) ras = raster_token_of_position(g, (int)pos);
+    uint4 v[CPR];
+#pragma unroll
+    for (int j = 0; j < CPR; ++j) {
+      const int r = j * RPI + sub;                            // row of this lane in the wave's 64
+      const int64_t rp = p0 + r;
+      const int64_t rr = __shfl(ras, r);
+      const int64_t from = direction == 0 ? rr : rp;
+      v[j] = make_uint4(0, 0, 0, 0);
+      if (rp < dm.t) v[j] = *reinterpret_cast<const uint4*>(src + base + from * dm.st + 8 * c);
+    }
+#pragma unroll
+    for (int j = 0; j < CPR; ++j) {
+      const int r = j * RPI + sub;
+      const int64_t rp = p0 + r;
+      const int64_t rr = __shfl(ras, r);
+      const int64_t to = direction == 0 ? rp : rr;
+      if (rp < dm.t) *reinterpret_cast<uint4*>(dst + base + to * dm.st + 8 * c) = v[j];
+    }
   }
 }
 
@@ -34,10 +56,12 @@ __global__ __launch_bounds__(256) void reorder_kernel(Dims dm, TileGeom g, int d
 hipError_t launch_reorder(const Dims& dm, const int* grid, const int* tile, int direction, const uint16_t* src,
                           uint16_t* dst, hipStream_t s) {
   const TileGeom g = make_tile_geom(grid, tile, 0);
-  const int64_t chunks = dm.t * (dm.d / 8);
-  int64_t gx = (chunks + 255) / 256;
-  if (gx > 8192) gx = 8192;                                   // grid-stride beyond: 32 workgroups per CU and head
-  hipLaunchKernelGGL(reorder_kernel, dim3((unsigned)gx, dm.batch * dm.heads), dim3(256), 0, s, dm, g, direction, src, dst);
+  int64_t gx = (dm.t + 255) / 256;                            // 4 waves x 64 positions per workgroup
+  if (gx > 4096) gx = 4096;                                   // grid-stride beyond
+  if (dm.d == 128)
+    hipLaunchKernelGGL((reorder_kernel<16>), dim3((unsigned)gx, dm.batch * dm.heads), dim3(256), 0, s, dm, g, direction, src, dst);
+  else
+    hipLaunchKernelGGL((reorder_kernel<8>), dim3((unsigned)gx, dm.batch * dm.heads), dim3(256), 0, s, dm, g, direction, src, dst);
   return hipGetLastError();
 }
 
