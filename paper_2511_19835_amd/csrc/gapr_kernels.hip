@@ -11,13 +11,14 @@
 // block against all pooled vectors of the other side, so the cost is tokens x blocks x d.
 //
 // deviation_kernel: one workgroup per token block. The block is read once, centred on its
-// pooled vector (x_i - x^pool, fp32 subtraction, rounded to bf16) and parked in LDS; every
+// pooled vector (x_i - x^pool, fp32 subtraction, rounded to fp16) and parked in LDS; every
 // wave then keeps the whole centred block as the MFMA A operand in registers and walks the
 // pooled vectors of the other side 32 at a time, so the accumulators hold the deviations
 // themselves and the epilogue is one |.|-add per element. The pooled operand is rounded to
-// bf16 as well; accumulation is fp32. Both roundings perturb a product by ~2^-9 relative
-// with random sign: a few 1e-4 relative on DA / DB after the mean over the block's rows,
-// inside the band in which the gate is allowed to differ from fp64 arithmetic.
+// fp16 as well; accumulation is fp32. fp16 rather than bf16 because both operands are O(1)
+// quantities whose 2^-12 relative rounding leaves DA / DB within 2e-4 relative of fp64
+// arithmetic (bf16 operands: up to 1.5e-3, wider than the 1e-3 band in which the gate may
+// differ); the MFMA rate is the same. Conversions saturate at the largest finite half.
 #include "rsa_common.hpp"
 
 namespace rsa {
@@ -63,20 +64,20 @@ __global__ __launch_bounds__(256, 2) void deviation_kernel(Dims dm, const uint16
     for (int i = 0; i < BLK / RPP; ++i) {
       const int r = r0 + RPP * i;
       u32x4 c;
-      c.x = pack_bf16x2(bf16_bits_to_float(raw[i].x & 0xffffu) - m0[0], bf16_bits_to_float(raw[i].x >> 16) - m0[1]);
-      c.y = pack_bf16x2(bf16_bits_to_float(raw[i].y & 0xffffu) - m0[2], bf16_bits_to_float(raw[i].y >> 16) - m0[3]);
-      c.z = pack_bf16x2(bf16_bits_to_float(raw[i].z & 0xffffu) - m1[0], bf16_bits_to_float(raw[i].z >> 16) - m1[1]);
-      c.w = pack_bf16x2(bf16_bits_to_float(raw[i].w & 0xffffu) - m1[2], bf16_bits_to_float(raw[i].w >> 16) - m1[3]);
+      c.x = pack_f16x2_sat(bf16_bits_to_float(raw[i].x & 0xffffu) - m0[0], bf16_bits_to_float(raw[i].x >> 16) - m0[1]);
+      c.y = pack_f16x2_sat(bf16_bits_to_float(raw[i].y & 0xffffu) - m0[2], bf16_bits_to_float(raw[i].y >> 16) - m0[3]);
+      c.z = pack_f16x2_sat(bf16_bits_to_float(raw[i].z & 0xffffu) - m1[0], bf16_bits_to_float(raw[i].z >> 16) - m1[1]);
+      c.w = pack_f16x2_sat(bf16_bits_to_float(raw[i].w & 0xffffu) - m1[2], bf16_bits_to_float(raw[i].w >> 16) - m1[3]);
       if (r >= count) c = u32x4{0u, 0u, 0u, 0u};                // rows past a ragged block contribute nothing
       atile[swizzled<CPR>(r, cc)] = c;
     }
   }
   __syncthreads();
-  bf16x8 areg[MT][KS];
+  halfx8 areg[MT][KS];
 #pragma unroll
   for (int t = 0; t < MT; ++t)
 #pragma unroll
-    for (int s = 0; s < KS; ++s) areg[t][s] = __builtin_bit_cast(bf16x8, atile[swizzled<CPR>(32 * t + l32, 2 * s + hf)]);
+    for (int s = 0; s < KS; ++s) areg[t][s] = __builtin_bit_cast(halfx8, atile[swizzled<CPR>(32 * t + l32, 2 * s + hf)]);
 
   const float outscale = dm.scale / (float)count;
   float* orow = out + ((size_t)bh * n_blocks_x + xb) * n_other;
@@ -110,7 +111,7 @@ __global__ __launch_bounds__(256, 2) void deviation_kernel(Dims dm, const uint16
     for (int s = 0; s < KH; ++s)
 #pragma unroll
       for (int t = 0; t < MT; ++t)
-        acc[t] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(areg[t][s], __builtin_bit_cast(bf16x8, bpre[s]), acc[t], 0, 0, 0);
+        acc[t] = __builtin_amdgcn_mfma_f32_32x32x16_f16(areg[t][s], __builtin_bit_cast(halfx8, bpre[s]), acc[t], 0, 0, 0);
     __builtin_amdgcn_sched_barrier(0);
     if (o0 + 128 < n_other) {
       const uint16_t* pn = vec_ptr(o0 + 128);
@@ -121,7 +122,7 @@ __global__ __launch_bounds__(256, 2) void deviation_kernel(Dims dm, const uint16
     for (int s = 0; s < KH; ++s)
 #pragma unroll
       for (int t = 0; t < MT; ++t)
-        acc[t] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(areg[t][KH + s], __builtin_bit_cast(bf16x8, bcur[s]), acc[t], 0, 0, 0);
+        acc[t] = __builtin_amdgcn_mfma_f32_32x32x16_f16(areg[t][KH + s], __builtin_bit_cast(halfx8, bcur[s]), acc[t], 0, 0, 0);
     // every accumulator of a lane belongs to column o0 + l32; its rows are spread over the
     // registers and the two half-waves
     float dv = 0.f;

@@ -20,7 +20,7 @@ __device__ inline void accumulate8(float (&acc)[8], const uint4& v) {
 }
 
 // Reduce the per-thread partial sums over the row groups and write the block mean
-// (fp32) and, optionally, a bf16 copy.
+// (fp32) and, optionally, an fp16 copy (saturated; the gate GEMMs' pooled operand).
 template <int D, int RPP>
 __device__ inline void finish_mean(float (*red)[D], const float (&acc)[8], int r0, int cc, int count,
                                    float* mean_out, uint16_t* bf_out) {
@@ -34,7 +34,7 @@ __device__ inline void finish_mean(float (*red)[D], const float (&acc)[8], int r
     for (int r = 0; r < RPP; ++r) s += red[r][tid];
     const float mean = s / (float)count;
     mean_out[tid] = mean;
-    if (bf_out) bf_out[tid] = to_bf16_bits(mean);
+    if (bf_out) bf_out[tid] = to_f16_bits_sat(mean);
   }
 }
 

@@ -45,12 +45,22 @@ __device__ inline uint32_t pack_bf16x2(float a, float b) {
 }
 __device__ inline uint16_t to_bf16_bits(float a) { return (uint16_t)(pack_bf16x2(a, 0.f) & 0xffffu); }
 
+// fp16 (round-to-nearest-even), saturated to the largest finite half so that an out-of-range
+// value stays finite: the operands of the gate GEMMs carry 11 significant bits instead of 8.
+typedef _Float16 halfx2 __attribute__((ext_vector_type(2)));
+typedef _Float16 halfx8 __attribute__((ext_vector_type(8)));
+__device__ inline uint32_t pack_f16x2_sat(float a, float b) {
+  floatx2 f = {fminf(fmaxf(a, -65504.f), 65504.f), fminf(fmaxf(b, -65504.f), 65504.f)};
+  return __builtin_bit_cast(uint32_t, __builtin_convertvector(f, halfx2));
+}
+__device__ inline uint16_t to_f16_bits_sat(float a) { return (uint16_t)(pack_f16x2_sat(a, 0.f) & 0xffffu); }
+
 // ---- launchers (one per translation unit) -------------------------------------------
 struct PoolArgs {
   const uint16_t *Q, *K, *V;
   float *Qp, *Kp, *Vp;
   uint16_t* Vt;
-  uint16_t *Qpb, *Kpb;     // optional bf16 copies of the pooled vectors (operands of the gate GEMMs)
+  uint16_t *Qpb, *Kpb;     // optional fp16 copies of the pooled vectors (operands of the gate GEMMs)
 };
 hipError_t launch_pool(const Dims& dm, const PoolArgs& a, hipStream_t s);
 

@@ -79,6 +79,9 @@ CONFIGS = {
     "mid": LayerConfig("mid", 1, 24, 128, (13, 30, 52), 0, 128, 0.90),
     "wan": LayerConfig("wan", 1, 40, 128, (21, 45, 80), 0, 128, 0.90),
     "hunyuan": LayerConfig("hunyuan", 1, 24, 128, (33, 45, 80), 256, 128, 0.90),
+    # a 2-D image DiT shape (one latent frame of 256 x 256 tokens, 512 text tokens): stands in for the
+    # paper's 4K Flux.1-dev runs, which keep 10-25 % of the blocks
+    "flux": LayerConfig("flux", 1, 24, 128, (1, 256, 256), 512, 128, 0.90),
 }
 
 

@@ -290,3 +290,49 @@ def test_reorder_tokens_is_bit_exact(gpu, grid, tile, block, t_text, d, layout):
     assert np.array_equal(back, X)
     inv = gpu.reorder_tokens(X, tv, t_text, block, grid, tile, 1, layout)
     assert np.array_equal(inv[0, 1], ro.reorder_tokens(X[0, 1], grid, tile, 1))
+
+
+def _sampled_shape_check(gpu, cfg, heads, seed, sparsity, n_random=8, **kw):
+    """Full-size shape, a few heads: pooled tensors, masks, gates and factors in full, outputs on
+    sampled query blocks (first, ragged last video block, text blocks, some random ones)."""
+    import parity
+    Qb, Kb, Vb = synth.make_inputs(cfg, seed, heads=heads, workers=min(8, len(heads)), threads=True)
+    out = gpu.run_layer(Qb, Kb, Vb, cfg.t_video, cfg.t_text, cfg.block, sparsity, want_lse=False, **kw)
+    N, M = cfg.n_video_blocks, cfg.n_blocks
+    rng = np.random.default_rng(seed)
+    for i, h in enumerate(heads):
+        blocks = sorted(set([0, N - 1] + list(range(N, M)) + [int(x) for x in rng.integers(0, N, n_random)]))
+        ref = parity.oracle_head(Qb[0, i], Kb[0, i], Vb[0, i], cfg.t_video, cfg.t_text, cfg.block, sparsity,
+                                 query_blocks=blocks, **{k: v for k, v in kw.items() if k in ("p", "gapr_mode")})
+        st = parity.compare_head(out, 0, i, ref, Qb[0, i], Kb[0, i], Vb[0, i], query_blocks=blocks,
+                                 **{k: v for k, v in kw.items() if k in ("p",)})
+        print(f"  [{cfg.name} seed {seed} sparsity {sparsity} h{h}] {st}", flush=True)
+    return out
+
+
+def test_wan_shape_sampled(gpu):
+    """BASELINE config 2 (Wan-2.1-like: 21x45x80 = 75 600 video tokens, no text, block 128, 90 %),
+    three of its 40 heads."""
+    cfg = synth.CONFIGS["wan"]
+    out = _sampled_shape_check(gpu, cfg, [0, 19, 39], 0, cfg.sparsity)
+    assert (out["count"] == 591 - int(np.floor(0.9 * 591 + 1e-6))).all()
+
+
+@pytest.mark.parametrize("sparsity,seed,head", [(0.0, 0, 2), (0.5, 1, 5), (0.75, 2, 7), (0.85, 1, 11), (0.95, 2, 23)])
+def test_sparsity_sweep_at_hunyuan_shape(gpu, sparsity, seed, head):
+    """BASELINE config 4: the sparsity sweep at the config-3 shape (one head per point, seeds 0-2).
+    At sparsity 0 every block is critical: R = 1, nothing is compensated, output = dense attention."""
+    cfg = synth.CONFIGS["hunyuan"]
+    out = _sampled_shape_check(gpu, cfg, [head], seed, sparsity, n_random=4 if sparsity < 0.7 else 8)
+    k = 931 - int(np.floor(sparsity * 931 + 1e-6))
+    assert (out["count"] == k).all()
+    if sparsity == 0.0:
+        np.testing.assert_allclose(out["R"], 1.0, atol=2e-5)
+
+
+def test_image_shape_with_long_text_sampled(gpu):
+    """A 2-D image DiT shape (one latent frame, 256 x 256 tokens + 512 text tokens = 4 text blocks),
+    paper's image setting keeps 10 % of the blocks; full mask rule on top (p = 0.3)."""
+    cfg = synth.CONFIGS["flux"]
+    out = _sampled_shape_check(gpu, cfg, [1, 13], 0, 0.9, p=0.3)
+    assert (out["count"] >= 516 - int(np.floor(0.9 * 516 + 1e-6))).all()
