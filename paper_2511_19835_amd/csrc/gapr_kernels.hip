@@ -81,57 +81,52 @@ __global__ __launch_bounds__(256, 2) void deviation_kernel(Dims dm, const uint16
 
   const float outscale = dm.scale / (float)count;
   float* orow = out + ((size_t)bh * n_blocks_x + xb) * n_other;
-  const uint16_t* PBh = PB + (size_t)bh * n_other * D + 8 * hf;
+  // pooled vectors of the other side, fp16, in the layout of gate_operand_offset: the 32 vectors
+  // of one iteration and one k-step are 1 KB in a row, 16 bytes per lane
+  const uint16_t* PBh = PB + (size_t)bh * gate_operand_vectors(n_other) * D + 8 * lane;
 
   // The B operand of one iteration is 32 pooled vectors: lane (l32, hf) supplies channels
-  // 16s + 8hf .. +7 of vector o0 + l32 for k-step s. The first half of the k-steps is fetched
-  // one iteration ahead, the second half at the top of the iteration, behind the MFMAs of
-  // the first half.
-  constexpr int KH = KS / 2;
-  auto vec_ptr = [&](int o0) __attribute__((always_inline)) {
-    const int o = o0 + l32;
-    return PBh + (size_t)(o < n_other ? o : n_other - 1) * D;    // clamped: columns past the end are not stored
+  // 16s + 8hf .. +7 of vector o0 + l32 for k-step s. It is fetched a whole iteration ahead
+  // (two register sets that swap roles); to make room the block's row tiles are taken two at
+  // a time, so only 32 accumulator registers are live. Vectors past the end of the last group
+  // are padding: they only feed output columns that are never stored.
+  constexpr int TP = MT < 2 ? MT : 2;
+  auto load_vectors = [&](u32x4 (&dstv)[KS], int o0) __attribute__((always_inline)) {
+    const uint16_t* p = PBh + (size_t)(o0 / 32) * KS * 512;
+#pragma unroll
+    for (int s = 0; s < KS; ++s) dstv[s] = *reinterpret_cast<const u32x4*>(p + 512 * s);
   };
-  u32x4 bpre[KH], bcur[KH];
-  {
-    const uint16_t* p = vec_ptr(32 * wave);
-#pragma unroll
-    for (int s = 0; s < KH; ++s) bpre[s] = *reinterpret_cast<const u32x4*>(p + 16 * s);
-  }
-  for (int o0 = 32 * wave; o0 < n_other; o0 += 128) {
-    const uint16_t* p = vec_ptr(o0);
-#pragma unroll
-    for (int s = 0; s < KH; ++s) bcur[s] = *reinterpret_cast<const u32x4*>(p + 16 * (KH + s));
-    floatx16 acc[MT];
-#pragma unroll
-    for (int t = 0; t < MT; ++t)
-#pragma unroll
-      for (int r = 0; r < 16; ++r) acc[t][r] = 0.f;
-#pragma unroll
-    for (int s = 0; s < KH; ++s)
-#pragma unroll
-      for (int t = 0; t < MT; ++t)
-        acc[t] = __builtin_amdgcn_mfma_f32_32x32x16_f16(areg[t][s], __builtin_bit_cast(halfx8, bpre[s]), acc[t], 0, 0, 0);
-    __builtin_amdgcn_sched_barrier(0);
-    if (o0 + 128 < n_other) {
-      const uint16_t* pn = vec_ptr(o0 + 128);
-#pragma unroll
-      for (int s = 0; s < KH; ++s) bpre[s] = *reinterpret_cast<const u32x4*>(pn + 16 * s);
-    }
-#pragma unroll
-    for (int s = 0; s < KH; ++s)
-#pragma unroll
-      for (int t = 0; t < MT; ++t)
-        acc[t] = __builtin_amdgcn_mfma_f32_32x32x16_f16(areg[t][KH + s], __builtin_bit_cast(halfx8, bcur[s]), acc[t], 0, 0, 0);
+  auto iteration = [&](const u32x4 (&bv)[KS], u32x4 (&bnext)[KS], int o0) __attribute__((always_inline)) {
+    if (o0 + 128 < n_other) load_vectors(bnext, o0 + 128);
     // every accumulator of a lane belongs to column o0 + l32; its rows are spread over the
-    // registers and the two half-waves
-    float dv = 0.f;
+    // registers, the row tiles and the two half-waves
+    float dv4[4] = {0.f, 0.f, 0.f, 0.f};       // four partial sums: no long chain of dependent adds
 #pragma unroll
-    for (int t = 0; t < MT; ++t)
+    for (int t0 = 0; t0 < MT; t0 += TP) {
+      floatx16 acc[TP];
 #pragma unroll
-      for (int r = 0; r < 16; ++r) dv += fabsf(acc[t][r]);
+      for (int t = 0; t < TP; ++t)
+#pragma unroll
+        for (int r = 0; r < 16; ++r) acc[t][r] = 0.f;
+#pragma unroll
+      for (int s = 0; s < KS; ++s)
+#pragma unroll
+        for (int t = 0; t < TP; ++t)
+          acc[t] = __builtin_amdgcn_mfma_f32_32x32x16_f16(areg[t0 + t][s], __builtin_bit_cast(halfx8, bv[s]), acc[t], 0, 0, 0);
+#pragma unroll
+      for (int t = 0; t < TP; ++t)
+#pragma unroll
+        for (int r = 0; r < 16; ++r) dv4[r % 4] += fabsf(acc[t][r]);
+    }
+    float dv = (dv4[0] + dv4[1]) + (dv4[2] + dv4[3]);
     dv += __shfl_xor(dv, 32);
     if (hf == 0 && o0 + l32 < n_other) orow[o0 + l32] = dv * outscale;
+  };
+  u32x4 b0[KS], b1[KS];
+  if (32 * wave < n_other) load_vectors(b0, 32 * wave);
+  for (int o0 = 32 * wave; o0 < n_other; o0 += 256) {
+    iteration(b0, b1, o0);
+    if (o0 + 128 < n_other) iteration(b1, b0, o0 + 128);
   }
 }
 

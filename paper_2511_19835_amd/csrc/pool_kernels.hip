@@ -23,7 +23,7 @@ __device__ inline void accumulate8(float (&acc)[8], const uint4& v) {
 // (fp32) and, optionally, an fp16 copy (saturated; the gate GEMMs' pooled operand).
 template <int D, int RPP>
 __device__ inline void finish_mean(float (*red)[D], const float (&acc)[8], int r0, int cc, int count,
-                                   float* mean_out, uint16_t* bf_out) {
+                                   float* mean_out, uint16_t* f16_base, int vec) {
 #pragma unroll
   for (int e = 0; e < 8; ++e) red[r0][cc * 8 + e] = acc[e];
   __syncthreads();
@@ -34,7 +34,7 @@ __device__ inline void finish_mean(float (*red)[D], const float (&acc)[8], int r
     for (int r = 0; r < RPP; ++r) s += red[r][tid];
     const float mean = s / (float)count;
     mean_out[tid] = mean;
-    if (bf_out) bf_out[tid] = to_f16_bits_sat(mean);
+    if (f16_base) f16_base[gate_operand_offset<D>(vec, tid)] = to_f16_bits_sat(mean);
   }
 }
 
@@ -65,10 +65,12 @@ __global__ __launch_bounds__(256) void pool_qk_kernel(Dims dm, PoolArgs a) {
 
   if (which == 0) {
     const size_t row = (size_t)bh * dm.n + m;
-    finish_mean<D, RPP>(red, acc, r0, cc, count, a.Qp + row * D, a.Qpb ? a.Qpb + row * D : nullptr);
+    finish_mean<D, RPP>(red, acc, r0, cc, count, a.Qp + row * D,
+                        a.Qpb ? a.Qpb + (size_t)bh * gate_operand_vectors(dm.n) * D : nullptr, m);
   } else {
     const size_t row = (size_t)bh * dm.m + m;
-    finish_mean<D, RPP>(red, acc, r0, cc, count, a.Kp + row * D, a.Kpb ? a.Kpb + row * D : nullptr);
+    finish_mean<D, RPP>(red, acc, r0, cc, count, a.Kp + row * D,
+                        a.Kpb ? a.Kpb + (size_t)bh * gate_operand_vectors(dm.m) * D : nullptr, m);
   }
 }
 
@@ -106,7 +108,7 @@ __global__ __launch_bounds__(256) void pool_v_kernel(Dims dm, PoolArgs a) {
     dst[0] = v[p].x; dst[1] = v[p].y; dst[2] = v[p].z; dst[3] = v[p].w;
   }
   const size_t row = (size_t)bh * dm.m + m;
-  finish_mean<D, RPP>(red, acc, r0, cc, count, a.Vp + row * D, nullptr);  // contains a barrier
+  finish_mean<D, RPP>(red, acc, r0, cc, count, a.Vp + row * D, nullptr, 0);  // contains a barrier
 
   // Each thread emits, for one pair of adjacent channels, 8 consecutive positions.
   uint16_t* out = a.Vt + row * (size_t)D * BLK;

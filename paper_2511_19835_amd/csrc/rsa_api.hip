@@ -49,8 +49,8 @@ PoolWs pool_ws_layout(const Dims& d) {
   size_t bh = (size_t)d.batch * d.heads;
   PoolWs w;
   size_t off = 0;
-  w.qpb = off; off += align256(bh * d.n * d.d * sizeof(uint16_t));
-  w.kpb = off; off += align256(bh * d.m * d.d * sizeof(uint16_t));
+  w.qpb = off; off += align256(bh * rsa::gate_operand_vectors(d.n) * d.d * sizeof(uint16_t));
+  w.kpb = off; off += align256(bh * rsa::gate_operand_vectors(d.m) * d.d * sizeof(uint16_t));
   w.da = off;   off += align256(bh * (size_t)d.n * d.m * sizeof(float));
   w.dbt = off;  off += align256(bh * (size_t)d.n * d.m * sizeof(float));
   w.total = off;

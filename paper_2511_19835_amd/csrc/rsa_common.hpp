@@ -55,12 +55,23 @@ __device__ inline uint32_t pack_f16x2_sat(float a, float b) {
 }
 __device__ inline uint16_t to_f16_bits_sat(float a) { return (uint16_t)(pack_f16x2_sat(a, 0.f) & 0xffffu); }
 
+// fp16 copies of the pooled vectors, laid out as the B operand of the gate GEMMs reads them:
+// vectors in groups of 32; for group g and k-step s (16 channels) the 64 lanes of a wave read
+// 1 KB in one piece -- lane = 32*hf + l32 holds channels 16s + 8hf .. +7 of vector 32g + l32.
+// Half-precision element offset of (vector o, channel c) inside one (batch, head):
+template <int D>
+__host__ __device__ inline size_t gate_operand_offset(int o, int c) {
+  return ((((size_t)(o / 32) * (D / 16) + c / 16) * 2 + (c % 16) / 8) * 32 + o % 32) * 8 + c % 8;
+}
+// vectors are padded to a multiple of 32 per (batch, head)
+__host__ __device__ inline size_t gate_operand_vectors(int n) { return (size_t)((n + 31) / 32) * 32; }
+
 // ---- launchers (one per translation unit) -------------------------------------------
 struct PoolArgs {
   const uint16_t *Q, *K, *V;
   float *Qp, *Kp, *Vp;
   uint16_t* Vt;
-  uint16_t *Qpb, *Kpb;     // optional fp16 copies of the pooled vectors (operands of the gate GEMMs)
+  uint16_t *Qpb, *Kpb;     // optional fp16 copies of the pooled vectors in gate_operand_offset layout
 };
 hipError_t launch_pool(const Dims& dm, const PoolArgs& a, hipStream_t s);
 
