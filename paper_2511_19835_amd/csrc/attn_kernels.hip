@@ -24,6 +24,7 @@
 // the long dense text rows start first and each XCD (workgroup id modulo 8) owns a
 // contiguous range of query blocks; two workgroups share a CU.
 #include "rsa_common.hpp"
+#include "lds_dma.hpp"
 
 namespace rsa {
 namespace {
@@ -93,26 +94,6 @@ __device__ __forceinline__ float half_wave_sum(float v) {
   return lo + hi;
 }
 
-// Direct-to-LDS loads (global_load_lds_dwordx4): every lane supplies the address of 16
-// bytes; lane L's data lands at lds_addr + 16*L, lds_addr wave-uniform (goes to M0). The
-// compiler does not track these loads: the caller waits with s_waitcnt vmcnt before the
-// barrier that publishes the buffer, and `fence` names the LDS buffer so that it counts as
-// written. Two address forms: scalar base + per-lane 32-bit byte offset, and per-lane pointer.
-__device__ __forceinline__ void dma16_sv(uint32_t lds_addr, const void* sbase, uint32_t voff, void* fence) {
-  // the base is wave-uniform by construction; make sure it sits in an SGPR pair
-  const uint64_t p = (uint64_t)(uintptr_t)sbase;
-  // (the builtin returns a signed int: widen through uint32_t, or the low word sign-extends)
-  const uint32_t p_lo = (uint32_t)__builtin_amdgcn_readfirstlane((uint32_t)p);
-  const uint32_t p_hi = (uint32_t)__builtin_amdgcn_readfirstlane((uint32_t)(p >> 32));
-  const uint64_t ps = ((uint64_t)p_hi << 32) | (uint64_t)p_lo;
-  asm volatile("s_mov_b32 m0, %0\n\tglobal_load_lds_dwordx4 %1, %2"
-               ::"s"(__builtin_amdgcn_readfirstlane(lds_addr)), "v"(voff), "s"(ps), "r"(fence) : "memory");
-}
-__device__ __forceinline__ void dma16_v(uint32_t lds_addr, const void* gptr, void* fence) {
-  asm volatile("s_mov_b32 m0, %0\n\tglobal_load_lds_dwordx4 %1, off"
-               ::"s"(__builtin_amdgcn_readfirstlane(lds_addr)), "v"(gptr), "r"(fence) : "memory");
-}
-
 // The running softmax reference is only raised when a row's new maximum exceeds it by
 // more than this many binades; probabilities then stay below 2^kLazyBits, which fp32 sums
 // and bf16 operands hold without loss, and the accumulators are rescaled rarely.
@@ -120,12 +101,6 @@ constexpr float kLazyBits = 6.0f;
 
 template <int V>
 struct IntC { static constexpr int value = V; };
-
-template <int NLEFT>
-__device__ __forceinline__ void wait_loads_leaving() {
-  // vmcnt(NLEFT): bits 3:0 and 15:14 hold the count, exp/lgkm fields stay at "no wait"
-  __builtin_amdgcn_s_waitcnt(0x0F70 | (NLEFT & 15) | ((NLEFT >> 4) << 14));
-}
 
 template <int D, int BLK>
 __global__ __launch_bounds__(64 * BLK / 32, (BLK == 128 ? 2 : 1)) void attn_kernel(Dims dm, AttnArgs a, int n_text_items,
