@@ -163,10 +163,12 @@ int rsa_adjacency_mask(const rsa_shape* shape, const int32_t* grid, const int32_
  * receives the natural-log softmax denominator (including the row maximum) of the
  * un-rectified sparse/dense attention of every row.
  * With RSA_DENSE every list/mask/R/Apool/Mc/Vp pointer may be NULL.
- * ws / ws_bytes: device scratch of at least attn_ws_bytes, 256-byte aligned; it receives the
- * pooled compensation term C_n (fp32 [b][h][N][d], Alg. 1 step 21) before the attention
- * kernel reads it back. Required with RSA_COMPENSATE (RSA_E_NULL / RSA_E_WORKSPACE otherwise),
- * ignored and may be NULL without it. The caller owns it; its contents afterwards are unspecified.
+ * ws / ws_bytes: device scratch of at least attn_ws_bytes, 256-byte aligned (RSA_E_WORKSPACE
+ * otherwise). It receives the pooled compensation term C_n (fp32 [b][h][N][d], Alg. 1 step 21)
+ * and the order in which the video query blocks are launched (rows with similar lists next to
+ * each other, so that they share K/V tiles in the L2 of their XCD; the results do not depend on
+ * it). Required with RSA_COMPENSATE (RSA_E_NULL); without that flag it may be NULL, and the rows
+ * are then launched in index order. The caller owns it; its contents afterwards are unspecified.
  */
 int rsa_sparse_attn_rectified(const rsa_shape* shape, const void* Q, const void* K, const void* Vt,
                               const int32_t* block_idx, const int32_t* count,

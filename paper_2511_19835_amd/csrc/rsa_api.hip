@@ -57,9 +57,13 @@ PoolWs pool_ws_layout(const Dims& d) {
   return w;
 }
 
-// rsa_sparse_attn_rectified scratch: the pooled compensation term C_n, fp32 [b][h][N][d].
-size_t attn_ws_size(const Dims& d) {
+// rsa_sparse_attn_rectified scratch: the pooled compensation term C_n, fp32 [b][h][N][d], then
+// the launch order of the video query blocks, int32 [b][h][N].
+size_t attn_ws_comp_bytes(const Dims& d) {
   return align256((size_t)d.batch * d.heads * d.n * d.d * sizeof(float));
+}
+size_t attn_ws_size(const Dims& d) {
+  return attn_ws_comp_bytes(d) + align256((size_t)d.batch * d.heads * d.n * sizeof(int32_t));
 }
 
 }  // namespace
@@ -189,15 +193,15 @@ int rsa_sparse_attn_rectified(const rsa_shape* shape, const void* Q, const void*
     if (!block_idx || !count) return RSA_E_NULL;
     if ((flags & RSA_RECTIFY_CRITICAL) && !R) return RSA_E_NULL;
     if ((flags & RSA_COMPENSATE) && (!mask_bits || !Apool || !Mc_bits || !Vp)) return RSA_E_NULL;
-    if (flags & RSA_COMPENSATE) {
-      if (!ws) return RSA_E_NULL;
-      if (ws_bytes < attn_ws_size(d) || ((uintptr_t)ws & 255)) return RSA_E_WORKSPACE;
-    }
+    if ((flags & RSA_COMPENSATE) && !ws) return RSA_E_NULL;
+    if (ws && (ws_bytes < attn_ws_size(d) || ((uintptr_t)ws & 255))) return RSA_E_WORKSPACE;
   }
   rsa::AttnArgs aa;
   aa.Q = (const uint16_t*)Q; aa.K = (const uint16_t*)K; aa.Vt = (const uint16_t*)Vt;
   aa.block_idx = block_idx; aa.count = count; aa.mask_bits = mask_bits; aa.Mc_bits = Mc_bits;
-  aa.R = R; aa.Apool = Apool; aa.Vp = Vp; aa.O = (uint16_t*)O; aa.lse = lse; aa.comp = (float*)ws; aa.flags = flags;
+  aa.R = R; aa.Apool = Apool; aa.Vp = Vp; aa.O = (uint16_t*)O; aa.lse = lse; aa.comp = (float*)ws;
+  aa.row_order = (ws && !(flags & RSA_DENSE)) ? (int32_t*)((char*)ws + attn_ws_comp_bytes(d)) : nullptr;
+  aa.flags = flags;
   if (rsa::launch_attn(d, aa, (hipStream_t)stream) != hipSuccess) return RSA_E_LAUNCH;
   return RSA_OK;
 }

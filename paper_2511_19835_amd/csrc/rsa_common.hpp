@@ -118,6 +118,7 @@ struct AttnArgs {
   uint16_t* O;
   float* lse;
   float* comp;             // workspace [b][h][N][d]: pooled compensation term C_n
+  int32_t* row_order;      // workspace [b][h][N]: launch order of the video query blocks (NULL: natural)
   int flags;
 };
 hipError_t launch_attn(const Dims& dm, const AttnArgs& a, hipStream_t s);

@@ -40,7 +40,7 @@ def test_block_counts_and_workspace(lib):
     assert (n, m, w) == (929, 931, 30)
     pool_ws, attn_ws = rb.rsa_workspace_bytes(_shape())
     assert pool_ws > 0 and pool_ws % 256 == 0
-    assert attn_ws == 1 * 2 * 8 * 128 * 4
+    assert attn_ws == 1 * 2 * 8 * 128 * 4 + 256        # C_n, then the launch order (2 * 8 int32, padded to 256 B)
 
 
 @pytest.mark.parametrize("kw,code", [
