@@ -101,3 +101,26 @@ def reorder_tokens(X_bits: np.ndarray, t_video: int, t_text: int, block: int, gr
     rb.rsa_reorder_tokens(shape, grid, tile, direction, X, Y)
     torch.cuda.synchronize()
     return device_to_bits(Y)
+
+
+def run_layer_from_raster(Q_bits, K_bits, V_bits, grid, tile, t_text: int, block: int, sparsity: float,
+                          p: float = 0.0, use_adjacency: bool = False, device="cuda:0") -> np.ndarray:
+    """The whole sequence a caller with raster-ordered tokens runs, all on the device: reorder
+    Q, K, V into tile order, (optionally) generate the adjacency mask, the three layer calls, and
+    reorder O back. Returns O as bf16 bit patterns in raster order."""
+    t_video = int(grid[0]) * int(grid[1]) * int(grid[2])
+    Qr, Kr, Vr = (bits_to_device(x, device) for x in (Q_bits, K_bits, V_bits))
+    shape = rb.make_shape(Qr, t_video, t_text, block)
+    Q, K, V, O, Or = (torch.empty_like(Qr) for _ in range(5))
+    for src, dst in ((Qr, Q), (Kr, K), (Vr, V)):
+        rb.rsa_reorder_tokens(shape, grid, tile, 0, src, dst)
+    buf = rb.allocate(Q, t_video, t_text, block)
+    forced = None
+    if use_adjacency:
+        forced = torch.empty_like(buf.mask_bits)
+        rb.rsa_adjacency_mask(buf.shape, grid, tile, 1, forced)
+    rb.rectified_sparse_attention(Q, K, V, O, buf, sparsity, p, 1, forced,
+                                  rb.RSA_RECTIFY_CRITICAL | rb.RSA_COMPENSATE, None)
+    rb.rsa_reorder_tokens(shape, grid, tile, 1, O, Or)
+    torch.cuda.synchronize()
+    return device_to_bits(Or)

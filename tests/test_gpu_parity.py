@@ -336,3 +336,26 @@ def test_image_shape_with_long_text_sampled(gpu):
     cfg = synth.CONFIGS["flux"]
     out = _sampled_shape_check(gpu, cfg, [1, 13], 0, 0.9, p=0.3)
     assert (out["count"] >= 516 - int(np.floor(0.9 * 516 + 1e-6))).all()
+
+
+def test_raster_ordered_tokens_end_to_end(gpu):
+    """A caller with raster-ordered tokens: reorder in, adjacency mask, the three layer calls, reorder
+    out — against the oracle run the same way (its own tile order, adjacency mask and layer)."""
+    import parity
+    from oracle import rsa_oracle as ro
+    cfg = LayerConfig("raster", 1, 2, 64, (3, 12, 20), 40, 64, 0.6)
+    tile = synth.default_tile(cfg.block)
+    Qt, Kt, Vt = synth.make_inputs(cfg, 4)                       # drawn in tile order
+    to_raster = lambda X: np.stack([[ro.reorder_tokens(X[0, h], cfg.grid, tile, 1) for h in range(cfg.heads)]])
+    Qr, Kr, Vr = (to_raster(X) for X in (Qt, Kt, Vt))
+    O_gpu = gpu.run_layer_from_raster(Qr, Kr, Vr, cfg.grid, tile, cfg.t_text, cfg.block, cfg.sparsity,
+                                      p=0.3, use_adjacency=True)
+    part = ro.partition(cfg.t_video, cfg.t_text, cfg.block)
+    adja = ro.adjacency_mask(synth.tile_order_coords(cfg.grid, cfg.block, tile), tile, part, 1)
+    for h in range(cfg.heads):
+        Q, K, V = (ro.reorder_tokens(ro.bf16_bits_to_f64(X[0, h]), cfg.grid, tile, 0) for X in (Qr, Kr, Vr))
+        ref = ro.rectified_layer_head(Q, K, V, cfg.t_video, cfg.t_text, cfg.block, cfg.sparsity, p=0.3, forced=adja)
+        O_ref = ro.reorder_tokens(ref["O"], cfg.grid, tile, 1)
+        err = ro.bf16_bits_to_f64(O_gpu[0, h]) - O_ref
+        assert np.abs(err).max() <= parity.OUT_MAX_ABS
+        assert np.linalg.norm(err) / np.linalg.norm(O_ref) <= parity.OUT_REL_L2
