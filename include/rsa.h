@@ -108,6 +108,16 @@ int rsa_pool(const rsa_shape* shape, const void* Q, const void* K, const void* V
              void* ws, size_t ws_bytes, void* stream);
 
 /*
+ * The value part of rsa_pool alone (Alg. 1 step 3 for V): Vp and the channel-major copy Vt of a
+ * new V, nothing else. For callers that keep the masks, lists, factors and A^pool of an earlier
+ * call (the paper combines the method with caches across diffusion steps, Sec. 5 and appendix
+ * "Implementations") and only
+ * attend again with new tensors: rsa_pool_values(V') then rsa_sparse_attn_rectified(Q', K', Vt', ...).
+ * Same layouts and ownership as in rsa_pool; Vp and Vt are fully overwritten.
+ */
+int rsa_pool_values(const rsa_shape* shape, const void* V, float* Vp, void* Vt, void* stream);
+
+/*
  * Alg. 1 steps 13-14 and 19, per video query block n:
  *   keep the k = clamp(M - floor(sparsity*M + 1e-6), 1, M) blocks of largest Lmass (equal
  *   keys: lower block index first); if p > 0 extend, in the same descending order, until

@@ -23,7 +23,7 @@ RSA_DENSE = 4
 RSA_MAX_BLOCKS = 4096
 
 EXPORTS = (
-    "rsa_block_counts", "rsa_workspace_bytes", "rsa_pool", "rsa_adjacency_mask", "rsa_reorder_tokens", "rsa_select_blocks",
+    "rsa_block_counts", "rsa_workspace_bytes", "rsa_pool", "rsa_pool_values", "rsa_adjacency_mask", "rsa_reorder_tokens", "rsa_select_blocks",
     "rsa_sparse_attn_rectified", "rsa_status_string",
 )
 
@@ -65,6 +65,8 @@ def _lib() -> ctypes.CDLL:
         lib.rsa_workspace_bytes.restype = ctypes.c_int
         lib.rsa_pool.argtypes = [shp] + [vp] * 11 + [ctypes.c_int, vp, ctypes.c_size_t, vp]
         lib.rsa_pool.restype = ctypes.c_int
+        lib.rsa_pool_values.argtypes = [shp, vp, vp, vp, vp]
+        lib.rsa_pool_values.restype = ctypes.c_int
         lib.rsa_select_blocks.argtypes = [shp, vp, vp, ctypes.c_double, ctypes.c_double, vp, vp, vp, vp, vp, vp]
         lib.rsa_select_blocks.restype = ctypes.c_int
         lib.rsa_sparse_attn_rectified.argtypes = [shp] + [vp] * 10 + [ctypes.c_int, vp, vp, vp, ctypes.c_size_t, vp]
@@ -127,6 +129,11 @@ def rsa_pool(shape, Q, K, V, Qp, Kp, Vp, Vt, Spool, Apool, Lmass, Mc_bits, gapr_
                            _ptr(Spool), _ptr(Apool), _ptr(Lmass), _ptr(Mc_bits), int(gapr_mode),
                            _ptr(ws), ws.numel() * ws.element_size() if ws is not None else 0,
                            _stream_ptr(stream)), "rsa_pool")
+
+
+def rsa_pool_values(shape, V, Vp, Vt, stream=None):
+    _check(_lib().rsa_pool_values(ctypes.byref(shape), _ptr(V), _ptr(Vp), _ptr(Vt), _stream_ptr(stream)),
+           "rsa_pool_values")
 
 
 def rsa_select_blocks(shape, Lmass, Apool, sparsity, p, forced_bits, mask_bits, block_idx, count, R, stream=None):

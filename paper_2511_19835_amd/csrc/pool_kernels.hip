@@ -133,7 +133,8 @@ __global__ __launch_bounds__(256) void pool_v_kernel(Dims dm, PoolArgs a) {
 template <int D, int BLK>
 hipError_t launch_pool_t(const Dims& dm, const PoolArgs& a, hipStream_t s) {
   const dim3 block(256);
-  hipLaunchKernelGGL((pool_qk_kernel<D, BLK>), dim3(dm.m, dm.batch * dm.heads, 2), block, 0, s, dm, a);
+  if (a.Q && a.K)    // values only: the caller keeps the pooled queries / keys of an earlier call
+    hipLaunchKernelGGL((pool_qk_kernel<D, BLK>), dim3(dm.m, dm.batch * dm.heads, 2), block, 0, s, dm, a);
   hipLaunchKernelGGL((pool_v_kernel<D, BLK>), dim3(dm.m, dm.batch * dm.heads, 1), block, 0, s, dm, a);
   return hipGetLastError();
 }

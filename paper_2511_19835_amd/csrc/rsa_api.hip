@@ -127,6 +127,17 @@ int rsa_pool(const rsa_shape* shape, const void* Q, const void* K, const void* V
   return RSA_OK;
 }
 
+int rsa_pool_values(const rsa_shape* shape, const void* V, float* Vp, void* Vt, void* stream) {
+  Dims d;
+  int rc = make_dims(shape, &d);
+  if (rc != RSA_OK) return rc;
+  if (!V || !Vp || !Vt) return RSA_E_NULL;
+  rsa::PoolArgs pa = {};
+  pa.V = (const uint16_t*)V; pa.Vp = Vp; pa.Vt = (uint16_t*)Vt;
+  if (rsa::launch_pool(d, pa, (hipStream_t)stream) != hipSuccess) return RSA_E_LAUNCH;
+  return RSA_OK;
+}
+
 int rsa_select_blocks(const rsa_shape* shape, const float* Lmass, const float* Apool,
                       double sparsity, double p, const uint32_t* forced_bits,
                       uint32_t* mask_bits, int32_t* block_idx, int32_t* count, float* R,

@@ -124,3 +124,23 @@ def run_layer_from_raster(Q_bits, K_bits, V_bits, grid, tile, t_text: int, block
     rb.rsa_reorder_tokens(shape, grid, tile, 1, O, Or)
     torch.cuda.synchronize()
     return device_to_bits(Or)
+
+
+def run_two_steps_reusing_masks(step1, step2, t_video: int, t_text: int, block: int, sparsity: float,
+                                device="cuda:0") -> dict:
+    """Step 1: the whole layer on (Q1, K1, V1). Step 2: only rsa_pool_values(V2) and the attention
+    call on (Q2, K2, V2), with the lists, factors, A^pool and gate bits step 1 left in the buffers.
+    Returns the step-1 mask / gate / R / A^pool and both outputs (bf16 bit patterns)."""
+    Q1, K1, V1 = (bits_to_device(x, device) for x in step1)
+    Q2, K2, V2 = (bits_to_device(x, device) for x in step2)
+    O1, O2 = torch.empty_like(Q1), torch.empty_like(Q2)
+    buf = rb.allocate(Q1, t_video, t_text, block)
+    flags = rb.RSA_RECTIFY_CRITICAL | rb.RSA_COMPENSATE
+    rb.rectified_sparse_attention(Q1, K1, V1, O1, buf, sparsity, 0.0, 1, None, flags, None)
+    rb.rsa_pool_values(buf.shape, V2, buf.Vp, buf.Vt)
+    rb.rsa_sparse_attn_rectified(buf.shape, Q2, K2, buf.Vt, buf.block_idx, buf.count, buf.mask_bits, buf.R,
+                                 buf.Apool, buf.Mc_bits, buf.Vp, flags, O2, None, buf.attn_ws)
+    torch.cuda.synchronize()
+    return dict(mask=unpack_bits(buf.mask_bits.cpu().numpy(), buf.M), Mc=unpack_bits(buf.Mc_bits.cpu().numpy(), buf.M),
+                R=buf.R.cpu().numpy(), Apool=buf.Apool.cpu().numpy(), Vp=buf.Vp.cpu().numpy(),
+                O1_bits=device_to_bits(O1), O2_bits=device_to_bits(O2))

@@ -359,3 +359,31 @@ def test_raster_ordered_tokens_end_to_end(gpu):
         err = ro.bf16_bits_to_f64(O_gpu[0, h]) - O_ref
         assert np.abs(err).max() <= parity.OUT_MAX_ABS
         assert np.linalg.norm(err) / np.linalg.norm(O_ref) <= parity.OUT_REL_L2
+
+
+def test_masks_reused_for_a_second_call(gpu):
+    """Pool and select once, attend twice: the second call sees new Q, K, V but the lists, factors,
+    A^pool and gate bits of the first (rsa_pool_values + rsa_sparse_attn_rectified only)."""
+    import parity
+    from oracle import rsa_oracle as ro
+    cfg = synth.CONFIGS["tiny"]
+    s1, s2 = synth.make_inputs(cfg, 0), synth.make_inputs(cfg, 1)
+    out = gpu.run_two_steps_reusing_masks(s1, s2, cfg.t_video, cfg.t_text, cfg.block, cfg.sparsity)
+    part = ro.partition(cfg.t_video, cfg.t_text, cfg.block)
+    scale = 1.0 / np.sqrt(cfg.head_dim)
+    for h in range(cfg.heads):
+        Q1, K1, V1 = (ro.bf16_bits_to_f64(x[0, h]) for x in s1)
+        Q2, K2, V2 = (ro.bf16_bits_to_f64(x[0, h]) for x in s2)
+        ref1 = ro.rectified_layer_head(Q1, K1, V1, cfg.t_video, cfg.t_text, cfg.block, cfg.sparsity)
+        assert np.array_equal(out["mask"][0, h], ref1["mask"]) and np.array_equal(out["Mc"][0, h], ref1["Mc"])
+        Vp2 = ro.pool(V2, part)
+        np.testing.assert_allclose(out["Vp"][0, h], Vp2, rtol=2e-6, atol=2e-6)
+        O_ref = np.empty_like(Q2)
+        O_spa = ro.sparse_attention(Q2, K2, V2, ref1["mask"], part, scale)
+        C = ro.compensation(ref1["A_pool"], ref1["mask"], ref1["Mc"], Vp2)
+        for n in range(part.n_video):
+            O_ref[part.tokens(n)] = ref1["R"][n] * O_spa[part.tokens(n)] + C[n][None, :]
+        O_ref[cfg.t_video:] = ro.dense_attention(Q2[cfg.t_video:], K2, V2, scale)
+        err = ro.bf16_bits_to_f64(out["O2_bits"][0, h]) - O_ref
+        assert np.abs(err).max() <= parity.OUT_MAX_ABS
+        assert np.linalg.norm(err) / np.linalg.norm(O_ref) <= parity.OUT_REL_L2
