@@ -387,3 +387,22 @@ def test_masks_reused_for_a_second_call(gpu):
         err = ro.bf16_bits_to_f64(out["O2_bits"][0, h]) - O_ref
         assert np.abs(err).max() <= parity.OUT_MAX_ABS
         assert np.linalg.norm(err) / np.linalg.norm(O_ref) <= parity.OUT_REL_L2
+
+
+def test_maximum_block_count(gpu):
+    """M = RSA_MAX_BLOCKS = 4096 key blocks (64 x 64 x 64 latent grid, block 64, one head of d 64):
+    the selection kernel's LDS keys, the launch-order sort and the mask words at their largest."""
+    cfg = LayerConfig("max", 1, 1, 64, (64, 64, 64), 0, 64, 0.99)
+    assert cfg.n_blocks == 4096
+    out = _sampled_shape_check(gpu, cfg, [0], 0, cfg.sparsity, n_random=6)
+    assert (out["count"] == 4096 - int(np.floor(0.99 * 4096 + 1e-6))).all()
+    assert out["mask_words"].shape[-1] == 128
+
+
+def test_one_block_more_than_the_maximum_is_refused(gpu):
+    import torch
+    from paper_2511_19835_amd import binding as rb
+    q = torch.zeros(1, 1, 4097 * 64, 64, dtype=torch.bfloat16, device="cuda:0")
+    with pytest.raises(rb.RsaError) as e:
+        rb.allocate(q, 4097 * 64, 0, 64)
+    assert e.value.status == -3
