@@ -26,56 +26,44 @@ __device__ inline float wave_sum(float v) {
   return v;
 }
 
-// 64 x 64 output tile per workgroup, 4 x 4 per thread, k in chunks of 32 through LDS.
+// One wave per 32 x 32 output tile, v_mfma_f32_32x32x2_f32: fp32 operands, fp32 products and
+// sums, so the scores keep full single precision (the selection that follows is compared with
+// fp64 inside a 1e-4 band). The contraction index may be visited in any order as long as both
+// operands agree: k-step s takes channel s from the lanes of the lower half-wave and channel
+// D/2 + s from the upper one, so every lane reads D/2 consecutive floats of its row.
 template <int D>
 __global__ __launch_bounds__(256) void pooled_scores_kernel(Dims dm, ScoreArgs a) {
-  constexpr int KC = 32;
-  __shared__ float qs[64][KC + 1];
-  __shared__ float ks[64][KC + 1];
+  constexpr int KH = D / 2;                     // k-steps; channels per half-wave
   const int bh = blockIdx.z;
-  const int n0 = blockIdx.y * 64, m0 = blockIdx.x * 64;
-  const float* Qp = a.Qp + (size_t)bh * dm.n * D;
-  const float* Kp = a.Kp + (size_t)bh * dm.m * D;
-  const int tx = threadIdx.x % 16, ty = threadIdx.x / 16;
-  float acc[4][4];
+  const int wave = threadIdx.x / 64, lane = threadIdx.x % 64;
+  const int l32 = lane % 32, hf = lane / 32;
+  const int n0 = blockIdx.y * 64 + (wave / 2) * 32, m0 = blockIdx.x * 64 + (wave % 2) * 32;
+  if (n0 >= dm.n || m0 >= dm.m) return;         // no barriers in this kernel
+  const int n = n0 + l32 < dm.n ? n0 + l32 : dm.n - 1;        // rows past the end repeat the last one (not stored)
+  const int m = m0 + l32 < dm.m ? m0 + l32 : dm.m - 1;
+  const floatx4* qrow = reinterpret_cast<const floatx4*>(a.Qp + ((size_t)bh * dm.n + n) * D + hf * KH);
+  const floatx4* krow = reinterpret_cast<const floatx4*>(a.Kp + ((size_t)bh * dm.m + m) * D + hf * KH);
+  floatx4 qv[KH / 4], kv[KH / 4];
 #pragma unroll
-  for (int i = 0; i < 4; ++i)
-#pragma unroll
-    for (int j = 0; j < 4; ++j) acc[i][j] = 0.f;
-
-  for (int k0 = 0; k0 < D; k0 += KC) {
-    // 64 rows x 32 floats per operand = 2048 floats, 8 per thread
-#pragma unroll
-    for (int i = 0; i < 8; ++i) {
-      const int idx = threadIdx.x + i * 256;
-      const int r = idx / KC, c = idx % KC;
-      qs[r][c] = (n0 + r < dm.n) ? Qp[(size_t)(n0 + r) * D + k0 + c] : 0.f;
-      ks[r][c] = (m0 + r < dm.m) ? Kp[(size_t)(m0 + r) * D + k0 + c] : 0.f;
-    }
-    __syncthreads();
-#pragma unroll
-    for (int kk = 0; kk < KC; ++kk) {
-      float qa[4], kb[4];
-#pragma unroll
-      for (int i = 0; i < 4; ++i) qa[i] = qs[ty * 4 + i][kk];
-#pragma unroll
-      for (int j = 0; j < 4; ++j) kb[j] = ks[tx * 4 + j][kk];
-#pragma unroll
-      for (int i = 0; i < 4; ++i)
-#pragma unroll
-        for (int j = 0; j < 4; ++j) acc[i][j] = fmaf(qa[i], kb[j], acc[i][j]);
-    }
-    __syncthreads();
+  for (int i = 0; i < KH / 4; ++i) {
+    qv[i] = qrow[i];
+    kv[i] = krow[i];
   }
+  floatx16 acc;
+#pragma unroll
+  for (int r = 0; r < 16; ++r) acc[r] = 0.f;
+  // A = pooled queries (M = query row), B = pooled keys (N = key column)
+#pragma unroll
+  for (int i = 0; i < KH / 4; ++i)
+#pragma unroll
+    for (int e = 0; e < 4; ++e) acc = __builtin_amdgcn_mfma_f32_32x32x2f32(qv[i][e], kv[i][e], acc, 0, 0, 0);
+  // accumulator register r: query row n0 + 8(r/4) + 4*hf + r%4, key column m0 + l32
   float* S = a.Spool + (size_t)bh * dm.n * dm.m;
+  if (m0 + l32 < dm.m) {
 #pragma unroll
-  for (int i = 0; i < 4; ++i) {
-    const int n = n0 + ty * 4 + i;
-    if (n >= dm.n) continue;
-#pragma unroll
-    for (int j = 0; j < 4; ++j) {
-      const int m = m0 + tx * 4 + j;
-      if (m < dm.m) S[(size_t)n * dm.m + m] = acc[i][j] * dm.scale;
+    for (int r = 0; r < 16; ++r) {
+      const int row = n0 + 8 * (r / 4) + 4 * hf + (r % 4);
+      if (row < dm.n) S[(size_t)row * dm.m + m0 + l32] = acc[r] * dm.scale;
     }
   }
 }
