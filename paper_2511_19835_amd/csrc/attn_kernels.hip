@@ -18,11 +18,13 @@
 // (computed beforehand by compensation_kernel into the workspace).
 //
 // 4*B*B*d flop per (query block, key block) pair against 2*B*d*2 bytes of K/V traffic.
-// Critical-block lists of neighbouring query blocks overlap little, so most of that
-// traffic misses the 4 MB L2 of an XCD and is served by the Infinity Cache / HBM path:
-// the kernel lives on keeping many tile loads in flight. Workgroups are ordered so that
-// the long dense text rows start first and each XCD (workgroup id modulo 8) owns a
-// contiguous range of query blocks; two workgroups share a CU.
+// Workgroups are ordered so that the long dense text rows start first and each XCD
+// (workgroup id modulo 8) owns a contiguous range of launch positions of a head;
+// row_order_kernel maps positions to video query blocks so that blocks with similar lists
+// are resident together and share K/V tiles in the XCD's L2. Two workgroups share a CU.
+// Measured: the matrix pipe is busy about 54 % of the cycles whatever the memory system does
+// (the softmax VALU work of a step is nearly as long as its MFMAs and overlaps them only
+// partly), and the core clock drops under the power cap while the kernel runs.
 #include "rsa_common.hpp"
 #include "lds_dma.hpp"
 
@@ -40,6 +42,9 @@ typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));
 #ifndef NSPLIT
 #define NSPLIT 1
 #endif
+// Build-time shape of the loop. Measured at the 128 x 128 configuration: 64 keys x 2 stages
+// (shipped) 18.5 ms; 32 x 2 at three waves per SIMD 18.5; 32 x 3 19.4; 32 x 4 20.8;
+// operands fetched from LDS in two halves per product (NSPLIT 2) 19.0.
 constexpr int KVS = RSA_KVS;        // keys per step
 constexpr int NSTAGE = RSA_NSTAGE;  // LDS ring depth
 
