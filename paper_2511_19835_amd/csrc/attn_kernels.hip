@@ -184,31 +184,51 @@ __global__ __launch_bounds__(64 * BLK / 32, (BLK == 128 ? 2 : 1)) void attn_kern
     const int j = s / C::SPB;
     return list ? clist[j] : j;
   };
-  // Request the K rows and the V^T rows of step s into ring stage `st`.
+  // Request the K rows and the V^T rows of step s into ring stage `st`. Everything that does
+  // not depend on the step is worked out once, in bytes, so that a step costs one scalar load,
+  // one 32 x 32 -> 64 bit multiply and a 64-bit add per load: the scalar instructions of a wave
+  // issue in order with its MFMAs and every one of them lengthens the step.
+  const uint32_t kblock_bytes = (uint32_t)BLK * (uint32_t)dm.st * 2u;       // K rows of consecutive key blocks
+  const uint32_t kstep_bytes = (uint32_t)KVS * (uint32_t)dm.st * 2u;        // ... of consecutive steps inside a block
+  const uint32_t kpass_bytes = (uint32_t)K_ROWS_PER_PASS * (uint32_t)dm.st * 2u;
+  const int64_t text_adjust = ((int64_t)dm.tv - (int64_t)dm.n * BLK) * dm.st * 2;   // text blocks start at T_v, not N*B
+  const int last_video_count = dm.block_count(dm.n - 1), last_count = dm.block_count(dm.m - 1);
+  const char* Kbytes = reinterpret_cast<const char*>(Kb);
+  const char* Vtbytes = reinterpret_cast<const char*>(Vtb);
+  constexpr uint32_t kVtBlockBytes = (uint32_t)D * BLK * 2u;
+  auto count_of = [&](int m) __attribute__((always_inline)) {
+    int c = BLK;
+    if (m == dm.n - 1) c = last_video_count;
+    if (m == dm.m - 1) c = last_count;
+    return c;
+  };
   auto issue_step = [&](int s, int st) __attribute__((always_inline)) {
-    const int m = block_of(s), part = s % C::SPB;
-    const int kv_count = dm.block_count(m);
-    const uint16_t* kblk = Kb + dm.block_start(m) * dm.st;
+    const int m = block_of(s);
+    const uint32_t part = (uint32_t)(s % C::SPB);
+    const int kv_count = count_of(m);
+    const char* kp = Kbytes + ((uint64_t)(uint32_t)m * kblock_bytes + (uint64_t)(m >= dm.n ? text_adjust : 0) +
+                               (uint64_t)(part * kstep_bytes));
+    const char* vp = Vtbytes + ((uint64_t)(uint32_t)m * kVtBlockBytes + part * (KVS * 2u));
     const uint32_t kdst = ldsK_addr + st * (C::STAGE * 16), vdst = ldsV_addr + st * (C::STAGE * 16);
     if (kv_count == BLK) {
 #pragma unroll
       for (int ii = 0; ii < C::KPW; ++ii)
-        dma16_sv(kdst + (ii / KOFF) * K_LDS_PASS + (ii % KOFF) * K_LDS_CLASS,
-                 kblk + (int64_t)(part * KVS + (ii / KOFF) * K_ROWS_PER_PASS) * dm.st, k_voff[ii % KOFF], lds);
+        dma16_sv(kdst + (ii / KOFF) * K_LDS_PASS + (ii % KOFF) * K_LDS_CLASS, kp + (ii / KOFF) * kpass_bytes,
+                 k_voff[ii % KOFF], lds);
     } else {
+      const char* kblk = kp - part * kstep_bytes;
 #pragma unroll
       for (int ii = 0; ii < C::KPW; ++ii) {
-        int r = part * KVS + (ii / KOFF) * K_ROWS_PER_PASS + k_r0[ii % KOFF];
+        int r = (int)part * KVS + (ii / KOFF) * K_ROWS_PER_PASS + k_r0[ii % KOFF];
         r = r < kv_count ? r : kv_count - 1;   // rows past a ragged block re-read its last row (masked later)
         dma16_sv(kdst + (ii / KOFF) * K_LDS_PASS + (ii % KOFF) * K_LDS_CLASS, kblk,
                  (uint32_t)((r * dm.st + k_col[ii % KOFF]) * 2), lds);
       }
     }
-    const uint16_t* vsrc = Vtb + (size_t)m * D * BLK + part * KVS;
 #pragma unroll
     for (int ii = 0; ii < C::VPW; ++ii)
       dma16_sv(vdst + (ii / VOFF) * V_LDS_PASS + (ii % VOFF) * V_LDS_CLASS,
-               vsrc + (size_t)((ii / VOFF) * V_ROWS_PER_PASS) * BLK, v_voff[ii % VOFF], lds);
+               vp + (ii / VOFF) * (V_ROWS_PER_PASS * BLK * 2), v_voff[ii % VOFF], lds);
   };
   constexpr int LPS = C::KPW + C::VPW;           // loads per step per wave
 
@@ -254,7 +274,7 @@ __global__ __launch_bounds__(64 * BLK / 32, (BLK == 128 ? 2 : 1)) void attn_kern
     if (s + NSTAGE - 2 < nsteps) wait_loads_leaving<(NSTAGE - 2) * LPS>(); else wait_loads_leaving<0>();
     __syncthreads();       // ... and everyone's; every wave is past step s-1, whose stage is free now
     if (s + NSTAGE - 1 < nsteps) issue_step(s + NSTAGE - 1, (ST + NSTAGE - 1) % NSTAGE);
-    const int kv_count = dm.block_count(block_of(s));
+    const int kv_count = count_of(block_of(s));
 
     // ---- S^T = K Q^T -------------------------------------------------------------------
     floatx16 sacc[C::KT];
