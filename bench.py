@@ -115,7 +115,7 @@ def cpu_baseline(cfg, sparsity, Qb, Kb, Vb, gpu_O_bits, gpu_mask, gpu_Mc, budget
 # (counter KiB x 1024 x the scale the same counter shows for a plain copy kernel: 2.0 fetch, 1.0 write).
 # A counter run cannot be made from inside the timed process, so the figure is carried here for the
 # exact workloads it was taken on and is null for any other.
-MEASURED_TRAFFIC_BYTES = {("hunyuan", 0.9, 0, 24): 33.10e6 * 2.0 * 1024 + 716.5e3 * 1024}
+MEASURED_TRAFFIC_BYTES = {("hunyuan", 0.9, 0, 24): 22.04e6 * 2.0 * 1024 + 857.2e3 * 1024}
 
 
 def measured_traffic(cfg, sparsity, args):

@@ -1,19 +1,27 @@
 // Block-sparse flash attention with the rectification fused into the epilogue
 // (paper Sec. 3.1 sparse attention, Alg. 1 steps 16-17; Sec. 4.1 / 4.2, Alg. 1 steps 19-23).
 //
-// One workgroup per (batch*head, query block), one wave per 32 query rows. Video query
-// blocks walk their compact, ascending list of critical key blocks; text query blocks
-// (and every block under RSA_DENSE) walk all M key blocks. Key blocks are consumed in steps
-// of KVS keys. For each step the K rows [KVS][d] and the channel-major V rows [d][KVS] are
-// brought into LDS by direct-to-LDS loads (global_load_lds_dwordx4: no staging registers)
-// into a ring of NSTAGE buffers, requested NSTAGE-1 steps ahead so that enough bytes are in
-// flight to cover the latency of the L2-miss path; one barrier per step hands a buffer
-// over. Each wave then computes, with v_mfma_f32_32x32x16_bf16,
+// A workgroup owns two query blocks of one (batch, head): two groups of BLK/32 waves, one wave
+// per 32 query rows, wave w of either group on the same SIMD. Video query blocks walk their
+// compact, ascending list of critical key blocks; text query blocks (and every block under
+// RSA_DENSE) walk all M key blocks. Key blocks are consumed in steps of KVS keys. For each
+// step the K rows [KVS][d] and the channel-major V rows [d][KVS] of a group are brought into
+// its own two-stage LDS ring by direct-to-LDS loads (global_load_lds_dwordx4: no staging
+// registers), one step ahead. Each wave computes, with v_mfma_f32_32x32x16_bf16,
 //     S^T = K Q^T      (M = key, N = query, k = channel)      -> accumulators: one query
 //     O^T += V^T P^T   (M = channel, N = query, k = key)         column per lane
 // so the online softmax is lane-local except for one exchange between the two half-waves,
 // and the probabilities a lane holds after the first product are exactly the B operand it
 // needs for the second (rsa_pool stores V in that key order).
+//
+// A step of a group is two phases, separated by workgroup barriers: an MFMA phase (the P V
+// product of the previous step, then K Q^T of this one: nothing but matrix instructions, LDS
+// operand reads a fixed number of slots ahead and the requests for the next tile, one per
+// slot) and a softmax phase (VALU only; it also moves the step's V^T operands to registers).
+// The two groups run one barrier apart, so that on every SIMD one wave feeds the matrix pipe
+// while the other uses the VALU. Measured against one workgroup per query block with the
+// softmax interleaved into each wave's own MFMA stream (two workgroups per CU): 14 % fewer
+// core cycles, 8 % less time (the clock drops further under the power cap).
 // Epilogue: O = R_n * acc / l + C_n, C_n = sum_{m: not kept and M_c} A^pool[n][m] v^pool_m
 // (computed beforehand by compensation_kernel into the workspace).
 //
@@ -21,10 +29,8 @@
 // Workgroups are ordered so that the long dense text rows start first and each XCD
 // (workgroup id modulo 8) owns a contiguous range of launch positions of a head;
 // row_order_kernel maps positions to video query blocks so that blocks with similar lists
-// are resident together and share K/V tiles in the XCD's L2. Two workgroups share a CU.
-// Measured: the matrix pipe is busy about 54 % of the cycles whatever the memory system does
-// (the softmax VALU work of a step is nearly as long as its MFMAs and overlaps them only
-// partly), and the core clock drops under the power cap while the kernel runs.
+// are resident together (the two of a workgroup are neighbours in that order) and share
+// K/V tiles in the XCD's L2.
 #include "rsa_common.hpp"
 #include "lds_dma.hpp"
 
@@ -39,19 +45,21 @@ typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));
 #ifndef RSA_NSTAGE
 #define RSA_NSTAGE 2
 #endif
-#ifndef NSPLIT
-#define NSPLIT 1
-#endif
-// Build-time shape of the loop. Measured at the 128 x 128 configuration: 64 keys x 2 stages
-// (shipped) 18.5 ms; 32 x 2 at three waves per SIMD 18.5; 32 x 3 19.4; 32 x 4 20.8;
-// operands fetched from LDS in two halves per product (NSPLIT 2) 19.0.
 constexpr int KVS = RSA_KVS;        // keys per step
-constexpr int NSTAGE = RSA_NSTAGE;  // LDS ring depth
+constexpr int NSTAGE = RSA_NSTAGE;  // LDS ring depth per group
+#ifndef RSA_VPRE
+#define RSA_VPRE 4
+#endif
+#ifndef RSA_MWIN
+#define RSA_MWIN 8
+#endif
+constexpr int MWIN = RSA_MWIN;      // MFMA slots between the LDS read of a K operand and its use
+constexpr int VPRE = RSA_VPRE;      // 16-key chunks of V^T operands fetched during the softmax (the rest: at the start of the MFMA phase)
 
 template <int D, int BLK>
 struct AttnCfg {
   static constexpr int NW = BLK / 32;       // waves per workgroup (one per 32 query rows)
-  static constexpr int NTHR = 64 * NW;
+  static constexpr int NTHR = 2 * 64 * NW;  // two groups of NW waves: two query blocks per workgroup
   static constexpr int SPB = BLK / KVS;     // steps per key block
   static constexpr int KT = KVS / 32;       // key tiles of S^T per step
   static constexpr int KS = D / 16;         // k-steps of K Q^T
@@ -67,7 +75,7 @@ struct AttnCfg {
   static constexpr int VBUF = D * VCPR;     // ... per V^T buffer
   static constexpr int STAGE = KBUF + VBUF; // one ring stage
   static_assert(KINST % NW == 0 && VINST % NW == 0, "loads must split evenly over the waves");
-  static_assert(NSTAGE >= 2 && NSTAGE * STAGE * 16 <= 80 * 1024, "ring must leave room for a second workgroup per CU");
+  static_assert(NSTAGE == 2 && 2 * NSTAGE * STAGE * 16 <= 160 * 1024, "two rings of two stages must fit the LDS of a CU");
 };
 
 // LDS tiles are unpadded; the 16-byte chunk c of row r is stored at chunk position
@@ -108,38 +116,57 @@ template <int V>
 struct IntC { static constexpr int value = V; };
 
 template <int D, int BLK>
-__global__ __launch_bounds__(64 * BLK / 32, (BLK == 128 ? 2 : 1)) void attn_kernel(Dims dm, AttnArgs a, int n_text_items,
+__global__ __launch_bounds__(2 * 64 * BLK / 32, 1) void attn_kernel(Dims dm, AttnArgs a, int n_text_items,
                                                                                   int chunk) {
   using C = AttnCfg<D, BLK>;
   constexpr int KBUF = C::KBUF;
-  __shared__ u32x4 lds[NSTAGE * C::STAGE];      // ring: stage st = [K rows | V^T rows]
+  __shared__ u32x4 lds_all[2 * NSTAGE * C::STAGE];   // per group a ring: stage st = [K rows | V^T rows]
 
   // ---- which (batch*head, query block) is this workgroup ---------------------------------
   const bool dense_all = (a.flags & RSA_DENSE) != 0;
-  int bh, qb;
+  const int tid = threadIdx.x;
+  const int wave_wg = __builtin_amdgcn_readfirstlane(tid / 64);
+  const int grp = wave_wg / C::NW;                   // which of the two query blocks of this workgroup
+  const int wave = wave_wg % C::NW;                  // wave inside the group (wave w of both groups shares a SIMD)
+  u32x4* lds = lds_all + grp * (NSTAGE * C::STAGE);
+  int bh;
+  int qb_of[2];                                      // query block of either group, -1: none
   {
     const int id = blockIdx.x;
-    if (id < n_text_items) {           // long dense rows first
-      const int per = dense_all ? dm.m : dm.mt;
-      bh = id / per;
-      qb = dense_all ? id % per : dm.n + id % per;
+    if (id < n_text_items) {           // long dense rows first, two per workgroup
+      const int per = dense_all ? dm.m : dm.mt, pairs = (per + 1) / 2;
+      bh = id / pairs;
+      const int r0 = 2 * (id % pairs), first = dense_all ? 0 : dm.n;
+      qb_of[0] = first + r0;
+      qb_of[1] = r0 + 1 < per ? first + r0 + 1 : -1;
     } else {
       const int v = id - n_text_items;
-      const int xcd = v & 7, j = v >> 3;
-      bh = j / chunk;
-      qb = xcd * chunk + j % chunk;
-      if (qb >= dm.n) return;          // whole workgroup leaves before any barrier
-      if (a.row_order) qb = a.row_order[(size_t)bh * dm.n + qb];   // launch position -> query block
+      const int xcd = v & 7, j = v >> 3, pairs = (chunk + 1) / 2;
+      bh = j / pairs;
+      const int p0 = xcd * chunk + 2 * (j % pairs);                 // launch positions p0, p0 + 1
+      const int pend = min(dm.n, (xcd + 1) * chunk);
+      if (p0 >= pend) return;          // whole workgroup leaves before any barrier
+#pragma unroll
+      for (int g = 0; g < 2; ++g) {
+        qb_of[g] = -1;
+        if (p0 + g < pend) qb_of[g] = a.row_order ? a.row_order[(size_t)bh * dm.n + p0 + g] : p0 + g;
+      }
     }
   }
+  auto steps_of = [&](int qbx) __attribute__((always_inline)) {
+    if (qbx < 0) return 0;
+    const bool sp = !dense_all && qbx < dm.n;
+    return (sp ? a.count[(size_t)bh * dm.n + qbx] : dm.m) * C::SPB;
+  };
+  const int smax = max(steps_of(qb_of[0]), steps_of(qb_of[1]));   // both groups turn the loop this often
+  const int qb = qb_of[grp] < 0 ? 0 : qb_of[grp];
+  const bool active = qb_of[grp] >= 0;
   const int b = bh / dm.heads, h = bh % dm.heads;
   const bool sparse_row = !dense_all && qb < dm.n;
   const size_t vrow = (size_t)bh * dm.n + qb;      // row of the per-video-block tensors
-  const int nlist = sparse_row ? a.count[vrow] : dm.m;
+  const int nlist = !active ? 0 : sparse_row ? a.count[vrow] : dm.m;
   const int32_t* list = sparse_row ? a.block_idx + vrow * dm.m : nullptr;
 
-  const int tid = threadIdx.x;
-  const int wave = __builtin_amdgcn_readfirstlane(tid / 64);   // wave-uniform: lives in an SGPR
   const int lane = tid % 64;
   const int l32 = lane % 32, hf = lane / 32;
   const int64_t base = (int64_t)b * dm.sb + (int64_t)h * dm.sh;
@@ -184,10 +211,10 @@ __global__ __launch_bounds__(64 * BLK / 32, (BLK == 128 ? 2 : 1)) void attn_kern
     const int j = s / C::SPB;
     return list ? clist[j] : j;
   };
-  // Request the K rows and the V^T rows of step s into ring stage `st`. Everything that does
-  // not depend on the step is worked out once, in bytes, so that a step costs one scalar load,
-  // one 32 x 32 -> 64 bit multiply and a 64-bit add per load: the scalar instructions of a wave
-  // issue in order with its MFMAs and every one of them lengthens the step.
+  // Requests for the K rows and the V^T rows of one step. Everything that does not depend on the
+  // step is worked out once, in bytes; a tile is prepared from its block index with scalar
+  // arithmetic only, and its LPS loads are then issued one at a time so that the caller can place
+  // them between its MFMAs.
   const uint32_t kblock_bytes = (uint32_t)BLK * (uint32_t)dm.st * 2u;       // K rows of consecutive key blocks
   const uint32_t kstep_bytes = (uint32_t)KVS * (uint32_t)dm.st * 2u;        // ... of consecutive steps inside a block
   const uint32_t kpass_bytes = (uint32_t)K_ROWS_PER_PASS * (uint32_t)dm.st * 2u;
@@ -202,35 +229,50 @@ __global__ __launch_bounds__(64 * BLK / 32, (BLK == 128 ? 2 : 1)) void attn_kern
     if (m == dm.m - 1) c = last_count;
     return c;
   };
-  auto issue_step = [&](int s, int st) __attribute__((always_inline)) {
-    const int m = block_of(s);
-    const uint32_t part = (uint32_t)(s % C::SPB);
-    const int kv_count = count_of(m);
-    const char* kp = Kbytes + ((uint64_t)(uint32_t)m * kblock_bytes + (uint64_t)(m >= dm.n ? text_adjust : 0) +
-                               (uint64_t)(part * kstep_bytes));
-    const char* vp = Vtbytes + ((uint64_t)(uint32_t)m * kVtBlockBytes + part * (KVS * 2u));
-    const uint32_t kdst = ldsK_addr + st * (C::STAGE * 16), vdst = ldsV_addr + st * (C::STAGE * 16);
-    if (kv_count == BLK) {
-#pragma unroll
-      for (int ii = 0; ii < C::KPW; ++ii)
-        dma16_sv(kdst + (ii / KOFF) * K_LDS_PASS + (ii % KOFF) * K_LDS_CLASS, kp + (ii / KOFF) * kpass_bytes,
-                 k_voff[ii % KOFF], lds);
+  constexpr int LPS = C::KPW + C::VPW;           // loads per step per wave
+  struct Tile {
+    const char* kp;       // K rows of this step
+    const char* kblk;     // K rows of the whole block (ragged path)
+    const char* vp;       // V^T rows of this step
+    uint32_t kdst, vdst;  // LDS byte addresses of the stage
+    int kv_count, part;
+  };
+  auto prepare_tile = [&](int m, int s, int st) __attribute__((always_inline)) {
+    Tile t;
+    t.part = s % C::SPB;
+    t.kv_count = count_of(m);
+    t.kblk = Kbytes + ((uint64_t)(uint32_t)m * kblock_bytes + (uint64_t)(m >= dm.n ? text_adjust : 0));
+    t.kp = t.kblk + (uint32_t)t.part * kstep_bytes;
+    t.vp = Vtbytes + ((uint64_t)(uint32_t)m * kVtBlockBytes + (uint32_t)t.part * (KVS * 2u));
+    t.kdst = ldsK_addr + st * (C::STAGE * 16);
+    t.vdst = ldsV_addr + st * (C::STAGE * 16);
+    return t;
+  };
+  // Load `idx` of a tile whose key block is full.
+  auto issue_load = [&](const Tile& t, int idx) __attribute__((always_inline)) {
+    if (idx < C::KPW) {
+      const int ii = idx;
+      dma16_sv(t.kdst + (ii / KOFF) * K_LDS_PASS + (ii % KOFF) * K_LDS_CLASS,
+               t.kp + (ii / KOFF) * kpass_bytes, k_voff[ii % KOFF], lds);
     } else {
-      const char* kblk = kp - part * kstep_bytes;
+      const int ii = idx - C::KPW;
+      dma16_sv(t.vdst + (ii / VOFF) * V_LDS_PASS + (ii % VOFF) * V_LDS_CLASS,
+               t.vp + (ii / VOFF) * (V_ROWS_PER_PASS * BLK * 2), v_voff[ii % VOFF], lds);
+    }
+  };
+  // All loads of a tile whose key block is ragged (the last video block, the last text block):
+  // K rows past the block end re-read its last row (masked later); V^T is zero-padded in HBM.
+  auto issue_ragged = [&](const Tile& t) __attribute__((always_inline)) {
 #pragma unroll
-      for (int ii = 0; ii < C::KPW; ++ii) {
-        int r = (int)part * KVS + (ii / KOFF) * K_ROWS_PER_PASS + k_r0[ii % KOFF];
-        r = r < kv_count ? r : kv_count - 1;   // rows past a ragged block re-read its last row (masked later)
-        dma16_sv(kdst + (ii / KOFF) * K_LDS_PASS + (ii % KOFF) * K_LDS_CLASS, kblk,
-                 (uint32_t)((r * dm.st + k_col[ii % KOFF]) * 2), lds);
-      }
+    for (int ii = 0; ii < C::KPW; ++ii) {
+      int r = t.part * KVS + (ii / KOFF) * K_ROWS_PER_PASS + k_r0[ii % KOFF];
+      r = r < t.kv_count ? r : t.kv_count - 1;
+      dma16_sv(t.kdst + (ii / KOFF) * K_LDS_PASS + (ii % KOFF) * K_LDS_CLASS, t.kblk,
+               (uint32_t)((r * dm.st + k_col[ii % KOFF]) * 2), lds);
     }
 #pragma unroll
-    for (int ii = 0; ii < C::VPW; ++ii)
-      dma16_sv(vdst + (ii / VOFF) * V_LDS_PASS + (ii % VOFF) * V_LDS_CLASS,
-               vp + (ii / VOFF) * (V_ROWS_PER_PASS * BLK * 2), v_voff[ii % VOFF], lds);
+    for (int ii = C::KPW; ii < LPS; ++ii) issue_load(t, ii);
   };
-  constexpr int LPS = C::KPW + C::VPW;           // loads per step per wave
 
   // ---- loop-invariant LDS read positions (16-byte chunk index inside stage 0, tile 0) ----
   const u32x4* kread[C::KS];
@@ -266,123 +308,224 @@ __global__ __launch_bounds__(64 * BLK / 32, (BLK == 128 ? 2 : 1)) void attn_kern
   float mref = -INFINITY, lpart = 0.f;   // softmax reference (log2 domain) and this lane's partial row sum
   const float cs = dm.scale * kLog2e;
 
-  // One step: KVS keys from ring stage ST (compile time, so every LDS offset is an
-  // immediate), after requesting step s + NSTAGE - 1 into the stage the previous step freed.
-  auto step = [&](auto stc, int s) __attribute__((always_inline)) {
+  // Two groups of waves share every SIMD (wave w of group 0 and wave w of group 1). They run
+  // the same sequence  [M(s) | barrier | V(s) | barrier] ...  one barrier apart, so that while
+  // one group issues MFMAs the other does its softmax on the VALU:
+  //   M(s): O^T += V^T P^T of step s-1 (operands already in registers), then S^T = K Q^T of step s
+  //         from ring stage s % 2; the loads of tile s+1 go out one per MFMA slot
+  //   V(s): fetch the V^T operands of step s into registers (their LDS latency hides behind the
+  //         softmax), mask, online softmax -> P as bf16 B operands; fetch the list entry of step
+  //         s+2; wait for tile s+1
+  // The barrier after V(s) publishes tile s+1 to the group and, because every LDS read of
+  // stage (s-1) % 2 has returned by then, frees that stage for the requests in M(s+1).
+  int m_nxt = 0;          // key block of the step after the current one
+  int kvc_cur = BLK;      // valid keys in the block of the current step
+  int kvc_nxt = BLK;
+  auto group_barrier = [&]() __attribute__((always_inline)) {
+    asm volatile("" ::: "memory");
+    __builtin_amdgcn_s_barrier();
+    asm volatile("" ::: "memory");
+  };
+  floatx16 sacc[C::KT];
+  u32x4 pb[C::PC];            // probabilities as bf16 B operands, 16 keys per entry
+  bf16x8 vop[C::PC][C::DT];   // V^T operands of the step whose P V product is still to come
+#pragma unroll
+  for (int pc = 0; pc < C::PC; ++pc) {
+    pb[pc] = u32x4{0u, 0u, 0u, 0u};
+#pragma unroll
+    for (int dt = 0; dt < C::DT; ++dt) vop[pc][dt] = __builtin_bit_cast(bf16x8, u32x4{0u, 0u, 0u, 0u});
+  }
+
+  // M(s) as one fixed sequence of NPV + NQK MFMA slots: the P V product of step s-1 (operands in
+  // registers, except the last chunks, read at the start), then K Q^T of step s. The K operand of
+  // slot i is read from LDS W slots ahead of its MFMA into a ring of W registers, so LDS latency
+  // stays behind MFMAs that already have their operands; the order is pinned slot by slot.
+  auto m_phase = [&](auto stc, auto pvc, auto qkc, int s) __attribute__((always_inline)) {
     constexpr int ST = decltype(stc)::value;
-    // this wave's share of step s has landed: all but the loads of the newer steps in flight
-    if (s + NSTAGE - 2 < nsteps) wait_loads_leaving<(NSTAGE - 2) * LPS>(); else wait_loads_leaving<0>();
-    __syncthreads();       // ... and everyone's; every wave is past step s-1, whose stage is free now
-    if (s + NSTAGE - 1 < nsteps) issue_step(s + NSTAGE - 1, (ST + NSTAGE - 1) % NSTAGE);
-    const int kv_count = count_of(block_of(s));
-
-    // ---- S^T = K Q^T -------------------------------------------------------------------
-    floatx16 sacc[C::KT];
+    constexpr bool do_pv = decltype(pvc)::value != 0, do_qk = decltype(qkc)::value != 0;
+    constexpr int NPV = C::PC * C::DT, NQK = C::KS * C::KT, NSLOT = NPV + NQK;
+    constexpr int W = MWIN;
+    constexpr int DSLOT = (VPRE < C::PC) ? (C::DT < NPV ? C::DT : 0) : 0;     // where the next tile is requested
+    const bool more = s + 1 < nsteps;
+    Tile nt = {};
+    if (more) nt = prepare_tile(m_nxt, s + 1, 1 - ST);      // m_nxt was fetched at the end of V(s-1)
+    kvc_nxt = nt.kv_count;
+    const bool full = nt.kv_count == BLK;
+    bf16x8 kring[W];
+    auto read_k = [&](int slot) __attribute__((always_inline)) {           // slot >= NPV
+      const int q = slot - NPV, k2 = q / C::KT, t = q % C::KT;
+      kring[slot % W] = __builtin_bit_cast(bf16x8, kread[k2][ST * C::STAGE + t * 32 * C::KCPR]);
+    };
+    if (do_pv) {
 #pragma unroll
-    for (int t = 0; t < C::KT; ++t)
+      for (int pc = VPRE; pc < C::PC; ++pc)
 #pragma unroll
-      for (int r = 0; r < 16; ++r) sacc[t][r] = 0.f;
-    constexpr int KSP = C::KS / NSPLIT;
-#pragma unroll
-    for (int h2 = 0; h2 < NSPLIT; ++h2) {
-      bf16x8 kop[KSP][C::KT];
-#pragma unroll
-      for (int k2 = 0; k2 < KSP; ++k2)
-#pragma unroll
-        for (int t = 0; t < C::KT; ++t)
-          kop[k2][t] = __builtin_bit_cast(bf16x8, kread[h2 * KSP + k2][ST * C::STAGE + t * 32 * C::KCPR]);
-#pragma unroll
-      for (int k2 = 0; k2 < KSP; ++k2)
-#pragma unroll
-        for (int t = 0; t < C::KT; ++t)
-          sacc[t] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(kop[k2][t], qreg[h2 * KSP + k2], sacc[t], 0, 0, 0);
-      __builtin_amdgcn_sched_barrier(0);
+        for (int dt = 0; dt < C::DT; ++dt)
+          vop[pc][dt] = __builtin_bit_cast(bf16x8, vread[pc][(1 - ST) * C::STAGE + dt * 32 * C::VCPR]);
     }
-
-    // accumulator register r of key tile t is key part*KVS + 32t + 8(r/4) + 4*hf + r%4 of the block
-    if (kv_count < BLK) {
-      const int part = s % C::SPB;
+    if (do_qk) {
 #pragma unroll
-      for (int t = 0; t < C::KT; ++t)
-#pragma unroll
-        for (int r = 0; r < 16; ++r) {
-          const int kv = part * KVS + 32 * t + 8 * (r / 4) + 4 * hf + (r % 4);
-          if (kv >= kv_count) sacc[t][r] = -INFINITY;
-        }
+      for (int j = NPV; j < W && j < NSLOT; ++j) read_k(j);
     }
-
-    // ---- online softmax, one query column per lane -----------------------------------
-    float mx = -INFINITY;
-#pragma unroll
-    for (int t = 0; t < C::KT; ++t)
-#pragma unroll
-      for (int r = 0; r < 16; ++r) mx = fmaxf(mx, sacc[t][r]);
-    mx = half_wave_max(mx) * cs;
-    if (__any(mx > mref + kLazyBits)) {
-      const float mnew = fmaxf(mref, mx);
-      const float alpha = __builtin_amdgcn_exp2f(mref - mnew);
-      mref = mnew;
-      lpart *= alpha;
-#pragma unroll
-      for (int dt = 0; dt < C::DT; ++dt)
-#pragma unroll
-        for (int r = 0; r < 16; ++r) oacc[dt][r] *= alpha;
-    }
-    const float moff = -mref;   // finite: the first step of a list always holds a valid key
-    u32x4 pb[C::PC];            // probabilities as bf16 B operands, 16 keys per entry
-    float rs = 0.f;
-#pragma unroll
-    for (int t = 0; t < C::KT; ++t) {
-      float p[16];
-#pragma unroll
-      for (int r = 0; r < 16; ++r) {
-        p[r] = __builtin_amdgcn_exp2f(fmaf(sacc[t][r], cs, moff));
-        rs += p[r];
-      }
-#pragma unroll
-      for (int u = 0; u < 2; ++u) {
-        u32x4 w;
-        w.x = pack_bf16x2(p[8 * u + 0], p[8 * u + 1]);
-        w.y = pack_bf16x2(p[8 * u + 2], p[8 * u + 3]);
-        w.z = pack_bf16x2(p[8 * u + 4], p[8 * u + 5]);
-        w.w = pack_bf16x2(p[8 * u + 6], p[8 * u + 7]);
-        pb[2 * t + u] = w;
-      }
-    }
-    lpart += rs;
     __builtin_amdgcn_sched_barrier(0);
-
-    // ---- O^T += V^T P^T ----------------------------------------------------------------
-    constexpr int PCP = C::PC / NSPLIT;
 #pragma unroll
-    for (int h2 = 0; h2 < NSPLIT; ++h2) {
-      bf16x8 vop[PCP][C::DT];
+    for (int i = 0; i < NSLOT; ++i) {
+      if (i == DSLOT && DSLOT > 0) __builtin_amdgcn_s_waitcnt(0xC07F);      // lgkmcnt(0): stage 1-ST is free
+      // one load of the tile of step s+1 per slot, behind the MFMA of the slot before
+      if (i == DSLOT && more && !full) issue_ragged(nt);
+      if (i >= DSLOT && i - DSLOT < LPS) {
+        if (more && full) issue_load(nt, i - DSLOT);
+      }
+      if (i < NPV) {
+        const int pc = i / C::DT, dt = i % C::DT;
+        if (do_pv)
+          oacc[dt] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(vop[pc][dt], __builtin_bit_cast(bf16x8, pb[pc]), oacc[dt], 0, 0, 0);
+      } else {
+        const int q = i - NPV, k2 = q / C::KT, t = q % C::KT;
+        if (do_qk) {
+          floatx16 c0 = sacc[t];
+          if (k2 == 0) {
 #pragma unroll
-      for (int p2 = 0; p2 < PCP; ++p2)
-#pragma unroll
-        for (int dt = 0; dt < C::DT; ++dt)
-          vop[p2][dt] = __builtin_bit_cast(bf16x8, vread[h2 * PCP + p2][ST * C::STAGE + dt * 32 * C::VCPR]);
-#pragma unroll
-      for (int p2 = 0; p2 < PCP; ++p2)
-#pragma unroll
-        for (int dt = 0; dt < C::DT; ++dt)
-          oacc[dt] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(vop[p2][dt], __builtin_bit_cast(bf16x8, pb[h2 * PCP + p2]),
-                                                             oacc[dt], 0, 0, 0);
+            for (int r = 0; r < 16; ++r) c0[r] = 0.f;           // folds into the instruction's constant C operand
+          }
+          sacc[t] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(kring[i % W], qreg[k2], c0, 0, 0, 0);
+        }
+      }
+      // the ring entry this slot used (or will never use) takes the operand of slot i + W
+      if (do_qk && i + W >= NPV && i + W < NSLOT) read_k(i + W);
       __builtin_amdgcn_sched_barrier(0);
     }
   };
 
-  // prologue: the first NSTAGE-1 steps are requested; then the ring turns one stage per step
+  auto v_phase = [&](auto stc, int s) __attribute__((always_inline)) {
+    constexpr int ST = decltype(stc)::value;
+    {
 #pragma unroll
-  for (int p = 0; p < NSTAGE - 1; ++p)
-    if (p < nsteps) issue_step(p, p);
-  for (int s = 0; s < nsteps; s += NSTAGE) {
-    step(IntC<0>{}, s);
-    if constexpr (NSTAGE > 1) { if (s + 1 < nsteps) step(IntC<1 % NSTAGE>{}, s + 1); }
-    if constexpr (NSTAGE > 2) { if (s + 2 < nsteps) step(IntC<2 % NSTAGE>{}, s + 2); }
-    if constexpr (NSTAGE > 3) { if (s + 3 < nsteps) step(IntC<3 % NSTAGE>{}, s + 3); }
-    static_assert(NSTAGE <= 4, "unroll the ring loop further for deeper rings");
+      for (int pc = 0; pc < VPRE; ++pc)
+#pragma unroll
+        for (int dt = 0; dt < C::DT; ++dt)
+          vop[pc][dt] = __builtin_bit_cast(bf16x8, vread[pc][ST * C::STAGE + dt * 32 * C::VCPR]);
+      __builtin_amdgcn_sched_barrier(0);
+      const int kv_count = kvc_cur;
+      // accumulator register r of key tile t is key part*KVS + 32t + 8(r/4) + 4*hf + r%4 of the block
+      if (kv_count < BLK) {
+        const int part = s % C::SPB;
+#pragma unroll
+        for (int t = 0; t < C::KT; ++t)
+#pragma unroll
+          for (int r = 0; r < 16; ++r) {
+            const int kv = part * KVS + 32 * t + 8 * (r / 4) + 4 * hf + (r % 4);
+            if (kv >= kv_count) sacc[t][r] = -INFINITY;
+          }
+      }
+      // ---- online softmax, one query column per lane ---------------------------------
+      float mx = -INFINITY;
+#pragma unroll
+      for (int t = 0; t < C::KT; ++t)
+#pragma unroll
+        for (int r = 0; r < 16; ++r) mx = fmaxf(mx, sacc[t][r]);
+      mx = half_wave_max(mx) * cs;
+      if (__any(mx > mref + kLazyBits)) {
+        const float mnew = fmaxf(mref, mx);
+        const float alpha = __builtin_amdgcn_exp2f(mref - mnew);
+        mref = mnew;
+        lpart *= alpha;
+#pragma unroll
+        for (int dt = 0; dt < C::DT; ++dt)
+#pragma unroll
+          for (int r = 0; r < 16; ++r) oacc[dt][r] *= alpha;
+      }
+      const float moff = -mref;   // finite: the first step of a list always holds a valid key
+      float rs = 0.f;
+#pragma unroll
+      for (int t = 0; t < C::KT; ++t) {
+        float p[16];
+#pragma unroll
+        for (int r = 0; r < 16; ++r) {
+          p[r] = __builtin_amdgcn_exp2f(fmaf(sacc[t][r], cs, moff));
+          rs += p[r];
+        }
+#pragma unroll
+        for (int u = 0; u < 2; ++u) {
+          u32x4 w;
+          w.x = pack_bf16x2(p[8 * u + 0], p[8 * u + 1]);
+          w.y = pack_bf16x2(p[8 * u + 2], p[8 * u + 3]);
+          w.z = pack_bf16x2(p[8 * u + 4], p[8 * u + 5]);
+          w.w = pack_bf16x2(p[8 * u + 6], p[8 * u + 7]);
+          pb[2 * t + u] = w;
+        }
+      }
+      lpart += rs;
+    }
+    // the list entry of step s+2 for M(s+1), fetched here so that its wait is the one below
+    m_nxt = s + 2 < nsteps ? block_of(s + 2) : 0;
+    kvc_cur = kvc_nxt;
+    // the probabilities are complete here: nothing of the softmax may sink behind the barrier
+    // into the MFMA phase, where it would take the other group's VALU time
+#pragma unroll
+    for (int pc = 0; pc < C::PC; ++pc) asm volatile("" : "+v"(pb[pc]));
+    asm volatile("" : "+v"(lpart), "+v"(mref));
+    // tile s+1 has landed (this wave's share; the barrier that follows covers the group), and
+    // every LDS read issued so far has returned, so stage ST may be overwritten after it
+    __builtin_amdgcn_s_waitcnt(0x0070);          // vmcnt(0), lgkmcnt(0)
+  };
+
+  if (nsteps > 0) {
+    const int m0 = block_of(0);
+    const Tile t0 = prepare_tile(m0, 0, 0);
+    if (t0.kv_count == BLK) {
+#pragma unroll
+      for (int i = 0; i < LPS; ++i) issue_load(t0, i);
+    } else {
+      issue_ragged(t0);
+    }
+    kvc_cur = t0.kv_count;
+    m_nxt = nsteps > 1 ? block_of(1) : 0;
   }
+  __builtin_amdgcn_s_waitcnt(0x0070);
+  group_barrier();                  // tile 0 of both groups is in LDS
+  if (grp == 1) group_barrier();    // group 1 runs one barrier behind group 0
+  // Every group turns smax + 1 rounds of two barriers; a round is M(s), V(s) while the group has
+  // steps left, the last P V product alone in round nsteps, and nothing but the barriers after.
+  using Y = IntC<1>;
+  using N = IntC<0>;
+  int s = 0;
+  if (nsteps > 0) {
+    m_phase(IntC<0>{}, N{}, Y{}, 0);
+    group_barrier();
+    v_phase(IntC<0>{}, 0);
+    group_barrier();
+    s = 1;
+    while (s + 1 < nsteps) {        // s is odd here
+      m_phase(IntC<1>{}, Y{}, Y{}, s);
+      group_barrier();
+      v_phase(IntC<1>{}, s);
+      group_barrier();
+      m_phase(IntC<0>{}, Y{}, Y{}, s + 1);
+      group_barrier();
+      v_phase(IntC<0>{}, s + 1);
+      group_barrier();
+      s += 2;
+    }
+    if (s < nsteps) {
+      m_phase(IntC<1>{}, Y{}, Y{}, s);
+      group_barrier();
+      v_phase(IntC<1>{}, s);
+      group_barrier();
+      s += 1;
+    }
+    if (s & 1) m_phase(IntC<1>{}, Y{}, N{}, s); else m_phase(IntC<0>{}, Y{}, N{}, s);
+    group_barrier();
+    group_barrier();
+    s += 1;
+  }
+  for (; s <= smax; ++s) {
+    group_barrier();
+    group_barrier();
+  }
+  if (grp == 0) group_barrier();
+
+  if (!active) return;      // no barrier follows
 
   // ---- epilogue: normalise, rectify, compensate, store ------------------------------------
   const bool do_comp = sparse_row && (a.flags & RSA_COMPENSATE);
@@ -522,9 +665,9 @@ hipError_t launch_attn_t(const Dims& dm, const AttnArgs& a, hipStream_t s) {
   using C = AttnCfg<D, BLK>;
   const int bh = dm.batch * dm.heads;
   const bool dense_all = (a.flags & RSA_DENSE) != 0;
-  const int n_text_items = dense_all ? bh * dm.m : bh * dm.mt;
+  const int n_text_items = bh * (((dense_all ? dm.m : dm.mt) + 1) / 2);       // workgroups of dense rows, two rows each
   const int chunk = (dm.n + 7) / 8;
-  const long long grid = (long long)n_text_items + (dense_all ? 0 : (long long)bh * 8 * chunk);
+  const long long grid = (long long)n_text_items + (dense_all ? 0 : (long long)bh * 8 * ((chunk + 1) / 2));
   if (grid <= 0 || grid > 0x7fffffffLL) return hipErrorInvalidValue;
   if (!dense_all && (a.flags & RSA_COMPENSATE))
     hipLaunchKernelGGL((compensation_kernel<D>), dim3((dm.n + kCompNQ - 1) / kCompNQ, bh), dim3(256), 0, s, dm, a);
