@@ -345,12 +345,10 @@ __global__ __launch_bounds__(2 * 64 * BLK / 32, 1) void attn_kernel(Dims dm, Att
     constexpr bool do_pv = decltype(pvc)::value != 0, do_qk = decltype(qkc)::value != 0;
     constexpr int NPV = C::PC * C::DT, NQK = C::KS * C::KT, NSLOT = NPV + NQK;
     constexpr int W = MWIN;
-    constexpr int DSLOT = (VPRE < C::PC) ? (C::DT < NPV ? C::DT : 0) : 0;     // where the next tile is requested
+    constexpr int DSLOT = (VPRE < C::PC) ? (C::DT < NPV ? C::DT : 1) : 1;     // where the next tile is requested
     const bool more = s + 1 < nsteps;
     Tile nt = {};
-    if (more) nt = prepare_tile(m_nxt, s + 1, 1 - ST);      // m_nxt was fetched at the end of V(s-1)
-    kvc_nxt = nt.kv_count;
-    const bool full = nt.kv_count == BLK;
+    bool full = true;
     bf16x8 kring[W];
     auto read_k = [&](int slot) __attribute__((always_inline)) {           // slot >= NPV
       const int q = slot - NPV, k2 = q / C::KT, t = q % C::KT;
@@ -370,7 +368,7 @@ __global__ __launch_bounds__(2 * 64 * BLK / 32, 1) void attn_kernel(Dims dm, Att
     __builtin_amdgcn_sched_barrier(0);
 #pragma unroll
     for (int i = 0; i < NSLOT; ++i) {
-      if (i == DSLOT && DSLOT > 0) __builtin_amdgcn_s_waitcnt(0xC07F);      // lgkmcnt(0): stage 1-ST is free
+      if (i == DSLOT && DSLOT > 1) __builtin_amdgcn_s_waitcnt(0xC07F);      // lgkmcnt(0): stage 1-ST is free
       // one load of the tile of step s+1 per slot, behind the MFMA of the slot before
       if (i == DSLOT && more && !full) issue_ragged(nt);
       if (i >= DSLOT && i - DSLOT < LPS) {
@@ -393,6 +391,14 @@ __global__ __launch_bounds__(2 * 64 * BLK / 32, 1) void attn_kernel(Dims dm, Att
       }
       // the ring entry this slot used (or will never use) takes the operand of slot i + W
       if (do_qk && i + W >= NPV && i + W < NSLOT) read_k(i + W);
+      if (i == 0) {
+        // behind the first MFMA, so that the matrix pipe starts as soon as the barrier opens:
+        // addresses of the tile of step s+1 (its list entry came in during V(s-1))
+        __builtin_amdgcn_sched_barrier(0);
+        if (more) nt = prepare_tile(m_nxt, s + 1, 1 - ST);
+        kvc_nxt = nt.kv_count;
+        full = nt.kv_count == BLK;
+      }
       __builtin_amdgcn_sched_barrier(0);
     }
   };
