@@ -139,6 +139,20 @@ def test_forced_keep_mask(gpu):
     assert (out["count"] >= 3).all()
 
 
+@pytest.mark.parametrize("name", ["d128_b64_text", "ragged_d64_b128", "batch2"])
+def test_rows_of_very_different_length(gpu, name):
+    """Every third video row is forced to keep all key blocks, its neighbours stay at the top-k
+    minimum: query blocks that share a workgroup then walk lists of very different length."""
+    cfg = EDGE[name]
+    N, M = cfg.n_video_blocks, cfg.n_blocks
+    forced = np.zeros((cfg.batch, cfg.heads, N, M), dtype=bool)
+    forced[:, :, 0::3, :] = True
+    out, _, _ = _run_and_compare(gpu, cfg, seed=12, sparsity=0.9, forced=forced)
+    assert (out["count"][:, :, 0::3] == M).all()
+    if N > 1:
+        assert out["count"][:, :, 1::3].max() < M
+
+
 def test_weight_threshold_extension(gpu):
     """p > 0 extends the kept prefix until the kept A^pool exceeds p (Alg. 1 step 13)."""
     import parity
