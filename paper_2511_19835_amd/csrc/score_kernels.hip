@@ -165,13 +165,62 @@ __global__ __launch_bounds__(256) void ipar_softmax_kernel(Dims dm, ScoreArgs a)
   for (int m = threadIdx.x; m < dm.m; m += 256) A[m] = expf(L[m] - mx) * inv;
 }
 
+// The same for rows of at most 64 * NI blocks: one wave per row, the row held in registers, so
+// every value is read once, every exponential is taken once and no barrier is needed.
+template <int NI>
+__global__ __launch_bounds__(256) void ipar_softmax_rows_kernel(Dims dm, ScoreArgs a) {
+  const int wave = threadIdx.x / 64, lane = threadIdx.x % 64;
+  const int n = blockIdx.x * 4 + wave, bh = blockIdx.y;
+  if (n >= dm.n) return;                         // no barriers in this kernel
+  const size_t row = ((size_t)bh * dm.n + n) * dm.m;
+  const float* S = a.Spool + row;
+  float* L = a.Lmass + row;
+  float* A = a.Apool + row;
+  const float ln_full = logf((float)dm.blk), ln_last = logf((float)dm.block_count(dm.n - 1));
+  float l[NI];
+  float mx = -INFINITY;
+#pragma unroll
+  for (int i = 0; i < NI; ++i) {
+    const int m = lane + 64 * i;
+    l[i] = -INFINITY;
+    if (m < dm.m) {
+      if (m < dm.n) {
+        l[i] = S[m] + (m == dm.n - 1 ? ln_last : ln_full);
+        L[m] = l[i];
+      } else {
+        l[i] = L[m];
+      }
+    }
+    mx = fmaxf(mx, l[i]);
+  }
+  mx = wave_max(mx);
+  float sum = 0.f;
+#pragma unroll
+  for (int i = 0; i < NI; ++i) {
+    l[i] = expf(l[i] - mx);                      // exp(-inf) = 0 for the slots past the row end
+    sum += l[i];
+  }
+  sum = wave_sum(sum);
+  const float inv = 1.0f / sum;
+#pragma unroll
+  for (int i = 0; i < NI; ++i) {
+    const int m = lane + 64 * i;
+    if (m < dm.m) A[m] = l[i] * inv;
+  }
+}
+
 template <int D, int BLK>
 hipError_t launch_scores_t(const Dims& dm, const ScoreArgs& a, hipStream_t s) {
   const int bh = dm.batch * dm.heads;
   hipLaunchKernelGGL((pooled_scores_kernel<D>), dim3((dm.m + 63) / 64, (dm.n + 63) / 64, bh), dim3(256), 0, s, dm, a);
   if (dm.tt > 0)
     hipLaunchKernelGGL((text_mass_kernel<D, BLK>), dim3((dm.n + 7) / 8, bh), dim3(256), 0, s, dm, a);
-  hipLaunchKernelGGL(ipar_softmax_kernel, dim3(dm.n, bh), dim3(256), 0, s, dm, a);
+  if (dm.m <= 64 * 4)
+    hipLaunchKernelGGL(ipar_softmax_rows_kernel<4>, dim3((dm.n + 3) / 4, bh), dim3(256), 0, s, dm, a);
+  else if (dm.m <= 64 * 16)
+    hipLaunchKernelGGL(ipar_softmax_rows_kernel<16>, dim3((dm.n + 3) / 4, bh), dim3(256), 0, s, dm, a);
+  else
+    hipLaunchKernelGGL(ipar_softmax_kernel, dim3(dm.n, bh), dim3(256), 0, s, dm, a);
   return hipGetLastError();
 }
 

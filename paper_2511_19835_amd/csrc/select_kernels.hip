@@ -2,12 +2,17 @@
 // Sec. 4.1 for R_n, Sec. 4.3 and the appendix "Implementations" for top-k and p).
 //
 // One wavefront per video query block. The row's M log-masses become order-preserving
-// 32-bit keys held in LDS, lane l owning blocks l, l+64, ...; the k-th largest key is found
+// 32-bit keys, lane l owning blocks l, l+64, ... (in registers for rows of at most 64 * NI
+// blocks, four rows per workgroup; in LDS for longer rows); the k-th largest key is found
 // by a 32-step bitwise search whose counts are wave ballots, so the selection is exact
 // integer work (ties: lower block index first). The optional weight threshold p extends
 // the kept prefix, in the same descending order, until the kept A^pool exceeds p.
 // Outputs: mask bits, ascending block list, count, and R_n = sum of kept A^pool.
 #include "rsa_common.hpp"
+
+// The loops over a row's slots carry an unroll request for the register form (fixed trip count);
+// the LDS form has a run-time trip count, where the request cannot be met and the compiler says so.
+#pragma clang diagnostic ignored "-Wpass-failed"
 
 namespace rsa {
 namespace {
@@ -33,35 +38,52 @@ __device__ inline float wave_inclusive_scan(float v, int lane) {
   return v;
 }
 
-__global__ __launch_bounds__(64) void select_kernel(Dims dm, SelectArgs a) {
+// NI > 0: keys and weights of a row in NI registers per lane, one row per wave of the workgroup.
+// NI == 0: in dynamic LDS, one row (one wave) per workgroup.
+template <int NI>
+__global__ __launch_bounds__(NI > 0 ? 256 : 64) void select_kernel(Dims dm, SelectArgs a) {
   extern __shared__ uint32_t smem[];
-  const int lane = threadIdx.x;
-  const int n = blockIdx.x, bh = blockIdx.y;
+  constexpr bool REG = NI > 0;
+  const int lane = threadIdx.x % 64;
+  const int n = REG ? blockIdx.x * 4 + (int)(threadIdx.x / 64) : blockIdx.x, bh = blockIdx.y;
+  if (n >= dm.n) return;                           // no barriers in this kernel
   const int M = dm.m;
-  const int slots = (M + 63) / 64;
-  uint32_t* keys = smem;
-  float* vals = reinterpret_cast<float*>(smem + slots * 64);
+  const int slots = REG ? NI : (M + 63) / 64;
   const size_t row = (size_t)bh * dm.n + n;
   const float* L = a.Lmass + row * M;
   const float* A = a.Apool + row * M;
+  uint32_t rk[REG ? NI : 1];
+  float rv[REG ? NI : 1];
+  uint32_t* keys = smem;
+  float* vals = reinterpret_cast<float*>(smem + (REG ? 0 : slots * 64));
+  auto key_at = [&](int s) __attribute__((always_inline)) { return REG ? rk[REG ? s : 0] : keys[s * 64 + lane]; };
+  auto val_at = [&](int s) __attribute__((always_inline)) { return REG ? rv[REG ? s : 0] : vals[s * 64 + lane]; };
 
+#pragma unroll
   for (int s = 0; s < slots; ++s) {
     const int m = s * 64 + lane;
-    keys[m] = (m < M) ? orderable_key(L[m]) : 0u;   // 0 sorts below every real key
-    vals[m] = (m < M) ? A[m] : 0.f;
+    const uint32_t k = (m < M) ? orderable_key(L[m]) : 0u;   // 0 sorts below every real key
+    const float v = (m < M) ? A[m] : 0.f;
+    if (REG) {
+      rk[REG ? s : 0] = k;
+      rv[REG ? s : 0] = v;
+    } else {
+      keys[m] = k;
+      vals[m] = v;
+    }
   }
-  // every lane only ever reads back the entries it wrote: no barrier needed
+  // (LDS form) every lane only ever reads back the entries it wrote: no barrier needed
 
   // k-th largest key
   uint32_t tau = 0;
   for (int bit = 31; bit >= 0; --bit) {
     const uint32_t cand = tau | (1u << bit);
     int cnt = 0;
-    for (int s = 0; s < slots; ++s) cnt += __popcll(__ballot(keys[s * 64 + lane] >= cand));
+    _Pragma("unroll") for (int s = 0; s < slots; ++s) cnt += __popcll(__ballot(key_at(s) >= cand));
     if (cnt >= a.keep) tau = cand;
   }
   int n_gt = 0;
-  for (int s = 0; s < slots; ++s) n_gt += __popcll(__ballot(keys[s * 64 + lane] > tau));
+  _Pragma("unroll") for (int s = 0; s < slots; ++s) n_gt += __popcll(__ballot(key_at(s) > tau));
   int ties = a.keep - n_gt;       // how many blocks equal to tau are kept (index order)
   int kept_target = a.keep;
 
@@ -71,22 +93,24 @@ __global__ __launch_bounds__(64) void select_kernel(Dims dm, SelectArgs a) {
     for (int bit = 31; bit >= 0; --bit) {
       const uint32_t cand = tau_p | (1u << bit);
       float part = 0.f;
-      for (int s = 0; s < slots; ++s) part += (keys[s * 64 + lane] >= cand) ? vals[s * 64 + lane] : 0.f;
+      _Pragma("unroll") for (int s = 0; s < slots; ++s) part += (key_at(s) >= cand) ? val_at(s) : 0.f;
       if (wave_sum(part) > a.p) tau_p = cand;
     }
     float part = 0.f;
     int n_gt_p = 0;
+#pragma unroll
     for (int s = 0; s < slots; ++s) {
-      const bool gt = keys[s * 64 + lane] > tau_p;
-      part += gt ? vals[s * 64 + lane] : 0.f;
+      const bool gt = key_at(s) > tau_p;
+      part += gt ? val_at(s) : 0.f;
       n_gt_p += __popcll(__ballot(gt));
     }
     float run = wave_sum(part);    // weight strictly above tau_p: not yet above p
     int ties_p = 0;
     if (tau_p != 0) {
+#pragma unroll
       for (int s = 0; s < slots; ++s) {
-        const bool tie = keys[s * 64 + lane] == tau_p;
-        const float tv = tie ? vals[s * 64 + lane] : 0.f;
+        const bool tie = key_at(s) == tau_p;
+        const float tv = tie ? val_at(s) : 0.f;
         const float incl = wave_inclusive_scan(tv, lane);
         ties_p += __popcll(__ballot(tie && (run + (incl - tv) <= a.p)));
         run += __shfl(incl, 63);
@@ -104,9 +128,10 @@ __global__ __launch_bounds__(64) void select_kernel(Dims dm, SelectArgs a) {
   int32_t* list = a.block_idx + row * M;
   int list_base = 0, tie_base = 0;
   float rpart = 0.f;
+#pragma unroll
   for (int s = 0; s < slots; ++s) {
     const int m = s * 64 + lane;
-    const uint32_t key = keys[m];
+    const uint32_t key = key_at(s);
     const bool tie = key == tau && m < M;
     const unsigned long long tie_mask = __ballot(tie);
     bool kept = (key > tau) || (tie && (tie_base + lanes_below(tie_mask) < ties));
@@ -117,7 +142,7 @@ __global__ __launch_bounds__(64) void select_kernel(Dims dm, SelectArgs a) {
     if ((lane & 31) == 0 && word < dm.w) mbits[word] = (uint32_t)(kept_mask >> (lane & 32));
     if (kept) {
       list[list_base + lanes_below(kept_mask)] = m;
-      rpart += vals[m];
+      rpart += val_at(s);
     }
     list_base += __popcll(kept_mask);
   }
@@ -131,9 +156,16 @@ __global__ __launch_bounds__(64) void select_kernel(Dims dm, SelectArgs a) {
 }  // namespace
 
 hipError_t launch_select(const Dims& dm, const SelectArgs& a, hipStream_t s) {
-  const int slots = (dm.m + 63) / 64;
-  const size_t lds = (size_t)slots * 64 * 2 * sizeof(uint32_t);
-  hipLaunchKernelGGL(select_kernel, dim3(dm.n, dm.batch * dm.heads), dim3(64), lds, s, dm, a);
+  const int bh = dm.batch * dm.heads;
+  if (dm.m <= 64 * 4) {
+    hipLaunchKernelGGL(select_kernel<4>, dim3((dm.n + 3) / 4, bh), dim3(256), 0, s, dm, a);
+  } else if (dm.m <= 64 * 16) {
+    hipLaunchKernelGGL(select_kernel<16>, dim3((dm.n + 3) / 4, bh), dim3(256), 0, s, dm, a);
+  } else {
+    const int slots = (dm.m + 63) / 64;
+    const size_t lds = (size_t)slots * 64 * 2 * sizeof(uint32_t);
+    hipLaunchKernelGGL(select_kernel<0>, dim3(dm.n, bh), dim3(64), lds, s, dm, a);
+  }
   return hipGetLastError();
 }
 
