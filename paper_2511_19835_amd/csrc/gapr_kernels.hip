@@ -12,9 +12,12 @@
 //
 // deviation_kernel: one workgroup per token block. The block is read once, centred on its
 // pooled vector (x_i - x^pool, fp32 subtraction, rounded to fp16) and parked in LDS; every
-// wave then keeps the whole centred block as the MFMA A operand in registers and walks the
-// pooled vectors of the other side 32 at a time, so the accumulators hold the deviations
-// themselves and the epilogue is one |.|-add per element. The pooled operand is rounded to
+// wave then walks the pooled vectors of the other side 32 at a time against the whole centred
+// block (the MFMA A operand, read from LDS just ahead of each MFMA), so the accumulators hold
+// the deviations themselves and the epilogue is one |.|-add per element. Three waves per SIMD.
+// Measured at the benchmark shape: 0.64 ms per side, 0.52 ms with the pooled-operand loads
+// switched off (they are 8 KB from L2 per 32 MFMAs and wave), 0.36 ms of MFMA time at the
+// clock the chip holds; a resident copy of the block in registers at two waves per SIMD: 0.65. The pooled operand is rounded to
 // fp16 as well; accumulation is fp32. fp16 rather than bf16 because both operands are O(1)
 // quantities whose 2^-12 relative rounding leaves DA / DB within 2e-4 relative of fp64
 // arithmetic (bf16 operands: up to 1.5e-3, wider than the 1e-3 band in which the gate may
@@ -25,19 +28,26 @@ namespace rsa {
 namespace {
 
 typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));
+#ifndef RSA_DEV_NT
+#define RSA_DEV_NT 256
+#endif
 
 // 16-byte chunk c of row r sits at chunk position c ^ key(r): 16 consecutive rows read at one
 // logical chunk index then touch every LDS bank once. CPR = chunks per row (8 or 16).
 template <int CPR>
 __device__ __forceinline__ int swizzled(int r, int c) { return r * CPR + (c ^ ((r / (16 / CPR)) & (CPR - 1))); }
 
-template <int D, int BLK>
-__global__ __launch_bounds__(256, 2) void deviation_kernel(Dims dm, const uint16_t* __restrict__ X,
+#ifndef RSA_DEV_OCC
+#define RSA_DEV_OCC 3
+#endif
+template <int D, int BLK, int NT>
+__global__ __launch_bounds__(NT, RSA_DEV_OCC) void deviation_kernel(Dims dm, const uint16_t* __restrict__ X,
                                                            const float* __restrict__ Xpool, int n_blocks_x,
                                                            const uint16_t* __restrict__ PB,
                                                            int n_other, float* __restrict__ out) {
   constexpr int MT = BLK / 32, KS = D / 16, CPR = D / 8;
-  constexpr int RPP = 256 / CPR;                 // rows staged per pass of the workgroup
+  constexpr int NW = NT / 64;                    // waves per workgroup
+  constexpr int RPP = NT / CPR;                  // rows staged per pass of the workgroup
   __shared__ u32x4 atile[BLK * CPR];
   const int xb = blockIdx.x, bh = blockIdx.y;
   const int b = bh / dm.heads, h = bh % dm.heads;
@@ -73,11 +83,13 @@ __global__ __launch_bounds__(256, 2) void deviation_kernel(Dims dm, const uint16
     }
   }
   __syncthreads();
-  halfx8 areg[MT][KS];
+  // the A operand of an MFMA is read from LDS just ahead of it: the registers that a resident copy
+  // of the block would take (128 at d = 128) buy a third wave per SIMD instead
+  const u32x4* arow[MT];
 #pragma unroll
-  for (int t = 0; t < MT; ++t)
-#pragma unroll
-    for (int s = 0; s < KS; ++s) areg[t][s] = __builtin_bit_cast(halfx8, atile[swizzled<CPR>(32 * t + l32, 2 * s + hf)]);
+  for (int t = 0; t < MT; ++t) arow[t] = atile + (32 * t + l32) * CPR;
+  const int akey = (l32 / (16 / CPR)) & (CPR - 1);
+#define RSA_DEV_A(t, s) __builtin_bit_cast(halfx8, arow[t][(2 * (s) + hf) ^ akey])
 
   const float outscale = dm.scale / (float)count;
   float* orow = out + ((size_t)bh * n_blocks_x + xb) * n_other;
@@ -97,7 +109,8 @@ __global__ __launch_bounds__(256, 2) void deviation_kernel(Dims dm, const uint16
     for (int s = 0; s < KS; ++s) dstv[s] = *reinterpret_cast<const u32x4*>(p + 512 * s);
   };
   auto iteration = [&](const u32x4 (&bv)[KS], u32x4 (&bnext)[KS], int o0) __attribute__((always_inline)) {
-    if (o0 + 128 < n_other) load_vectors(bnext, o0 + 128);
+    if (o0 + 32 * NW < n_other) load_vectors(bnext, o0 + 32 * NW);
+    asm volatile("" ::: "memory");      // the A operand is re-read every iteration: no hoisting into registers
     // every accumulator of a lane belongs to column o0 + l32; its rows are spread over the
     // registers, the row tiles and the two half-waves
     float dv4[4] = {0.f, 0.f, 0.f, 0.f};       // four partial sums: no long chain of dependent adds
@@ -112,7 +125,7 @@ __global__ __launch_bounds__(256, 2) void deviation_kernel(Dims dm, const uint16
       for (int s = 0; s < KS; ++s)
 #pragma unroll
         for (int t = 0; t < TP; ++t)
-          acc[t] = __builtin_amdgcn_mfma_f32_32x32x16_f16(areg[t0 + t][s], __builtin_bit_cast(halfx8, bv[s]), acc[t], 0, 0, 0);
+          acc[t] = __builtin_amdgcn_mfma_f32_32x32x16_f16(RSA_DEV_A(t0 + t, s), __builtin_bit_cast(halfx8, bv[s]), acc[t], 0, 0, 0);
 #pragma unroll
       for (int t = 0; t < TP; ++t)
 #pragma unroll
@@ -124,9 +137,9 @@ __global__ __launch_bounds__(256, 2) void deviation_kernel(Dims dm, const uint16
   };
   u32x4 b0[KS], b1[KS];
   if (32 * wave < n_other) load_vectors(b0, 32 * wave);
-  for (int o0 = 32 * wave; o0 < n_other; o0 += 256) {
+  for (int o0 = 32 * wave; o0 < n_other; o0 += 64 * NW) {
     iteration(b0, b1, o0);
-    if (o0 + 128 < n_other) iteration(b1, b0, o0 + 128);
+    if (o0 + 32 * NW < n_other) iteration(b1, b0, o0 + 32 * NW);
   }
 }
 
@@ -176,8 +189,9 @@ __global__ void fill_bits_kernel(Dims dm, uint32_t* bits, uint32_t value) {
 template <int D, int BLK>
 hipError_t launch_gapr_t(const Dims& dm, const GaprArgs& a, hipStream_t s) {
   const int bh = dm.batch * dm.heads;
-  hipLaunchKernelGGL((deviation_kernel<D, BLK>), dim3(dm.n, bh), dim3(256), 0, s, dm, a.Q, a.Qp, dm.n, a.Kpb, dm.m, a.DA);
-  hipLaunchKernelGGL((deviation_kernel<D, BLK>), dim3(dm.m, bh), dim3(256), 0, s, dm, a.K, a.Kp, dm.m, a.Qpb, dm.n, a.DBt);
+  constexpr int NT = RSA_DEV_NT;
+  hipLaunchKernelGGL((deviation_kernel<D, BLK, NT>), dim3(dm.n, bh), dim3(NT), 0, s, dm, a.Q, a.Qp, dm.n, a.Kpb, dm.m, a.DA);
+  hipLaunchKernelGGL((deviation_kernel<D, BLK, NT>), dim3(dm.m, bh), dim3(NT), 0, s, dm, a.K, a.Kp, dm.m, a.Qpb, dm.n, a.DBt);
   hipLaunchKernelGGL(gate_kernel, dim3(dm.w, (dm.n + 31) / 32, bh), dim3(256), 0, s, dm, a);
   return hipGetLastError();
 }
