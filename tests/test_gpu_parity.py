@@ -75,6 +75,14 @@ def test_mid_config_two_heads_parity(gpu):
     assert (out["count"] == 16).all()
 
 
+def test_peaky_inputs_parity(gpu):
+    """The same shape with the sinusoid amplitude doubled (pooled-score std about 4 instead of 1):
+    scores span a wider range, the softmax is peakier and the lazy rescale fires more often."""
+    cfg = synth.CONFIGS["mid"].with_(sigma_a=1.0)
+    _run_and_compare(gpu, cfg, seed=5, heads=[3])
+    _run_and_compare(gpu, cfg.with_(t_text=200), seed=6, heads=[1], sparsity=0.8)
+
+
 EDGE = {
     "ragged_d64_b128": LayerConfig("ragged_d64_b128", 1, 2, 64, (5, 9, 13), 77, 128, 0.6),
     "d128_b64_text": LayerConfig("d128_b64_text", 1, 2, 128, (4, 12, 10), 100, 64, 0.7),
