@@ -115,13 +115,13 @@ def cpu_baseline(cfg, sparsity, Qb, Kb, Vb, gpu_O_bits, gpu_mask, gpu_Mc, budget
 # (counter KiB x 1024 x the scale the same counter shows for a plain copy kernel: 2.0 fetch, 1.0 write).
 # A counter run cannot be made from inside the timed process, so the figure is carried here for the
 # exact workloads it was taken on and is null for any other.
-MEASURED_TRAFFIC_BYTES = {("hunyuan", 0.9, 0, 24): 22.04e6 * 2.0 * 1024 + 857.2e3 * 1024}
+MEASURED_TRAFFIC_BYTES = {("hunyuan", 0.9, 0, 24, 128, 128): 22.04e6 * 2.0 * 1024 + 857.2e3 * 1024}
 
 
 def measured_traffic(cfg, sparsity, args):
     if args.mask_rule != "topk":
         return None
-    return MEASURED_TRAFFIC_BYTES.get((cfg.name, round(float(sparsity), 6), args.seed, cfg.heads))
+    return MEASURED_TRAFFIC_BYTES.get((cfg.name, round(float(sparsity), 6), args.seed, cfg.heads, cfg.head_dim, cfg.block))
 
 
 def main():
@@ -133,6 +133,9 @@ def main():
     ap.add_argument("--sparsity", type=float, default=None)
     ap.add_argument("--seed", type=int, default=0)
     ap.add_argument("--heads", type=int, default=None, help="override the head count (smaller runs)")
+    ap.add_argument("--head-dim", type=int, default=None, choices=(64, 128),
+                    help="override the head dimension (the other kernel templates)")
+    ap.add_argument("--block", type=int, default=None, choices=(64, 128), help="override the block size B")
     ap.add_argument("--mask-rule", choices=("topk", "full"), default="topk",
                     help="topk: the k largest blocks per row (the configuration the metric is quoted on); "
                          "full: top-k, weight threshold p = 0.3 and the adjacency mask (paper's parameter table)")
@@ -150,6 +153,10 @@ def main():
     cfg = synth.CONFIGS[args.workload]
     if args.heads:
         cfg = cfg.with_(heads=args.heads)
+    if args.head_dim:
+        cfg = cfg.with_(head_dim=args.head_dim)
+    if args.block:
+        cfg = cfg.with_(block=args.block)
     sparsity = cfg.sparsity if args.sparsity is None else args.sparsity
     dev = "cuda:0"
 

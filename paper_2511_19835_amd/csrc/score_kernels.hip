@@ -4,7 +4,7 @@
 //
 //   pooled_scores_kernel   Spool[n][m] = scale * q^pool_n . k^pool_m       (N x M x d, tiny)
 //   text_mass_kernel       Lmass[n][N+i] = log sum_{t in text block i} exp(scale * q^pool_n . k_t)
-//   ipar_softmax_kernel    Lmass[n][m<N] = Spool + ln c_m ; Apool = row-softmax(Lmass)
+//   ipar_softmax_rows_kernel  Lmass[n][m<N] = Spool + ln c_m ; Apool = row-softmax(Lmass)
 //
 // softmax(Lmass) is the paper's reallocation written in log space: the mixed softmax
 // over [pooled video keys ; text tokens] gives weights proportional to exp(score); a video
@@ -132,41 +132,8 @@ __global__ __launch_bounds__(256) void text_mass_kernel(Dims dm, ScoreArgs a) {
   }
 }
 
-__global__ __launch_bounds__(256) void ipar_softmax_kernel(Dims dm, ScoreArgs a) {
-  __shared__ float red[8];
-  const int n = blockIdx.x, bh = blockIdx.y;
-  const size_t row = ((size_t)bh * dm.n + n) * dm.m;
-  const float* S = a.Spool + row;
-  float* L = a.Lmass + row;
-  float* A = a.Apool + row;
-  const int wave = threadIdx.x / 64, lane = threadIdx.x % 64;
-  float mx = -INFINITY;
-  for (int m = threadIdx.x; m < dm.m; m += 256) {
-    float l;
-    if (m < dm.n) {
-      l = S[m] + logf((float)dm.block_count(m));
-      L[m] = l;
-    } else {
-      l = L[m];
-    }
-    mx = fmaxf(mx, l);
-  }
-  mx = wave_max(mx);
-  if (lane == 0) red[wave] = mx;
-  __syncthreads();
-  mx = fmaxf(fmaxf(red[0], red[1]), fmaxf(red[2], red[3]));
-  float sum = 0.f;
-  for (int m = threadIdx.x; m < dm.m; m += 256) sum += expf(L[m] - mx);
-  sum = wave_sum(sum);
-  if (lane == 0) red[4 + wave] = sum;
-  __syncthreads();
-  sum = (red[4] + red[5]) + (red[6] + red[7]);
-  const float inv = 1.0f / sum;
-  for (int m = threadIdx.x; m < dm.m; m += 256) A[m] = expf(L[m] - mx) * inv;
-}
-
-// The same for rows of at most 64 * NI blocks: one wave per row, the row held in registers, so
-// every value is read once, every exponential is taken once and no barrier is needed.
+// One wave per row, the row held in registers (rows of at most 64 * NI blocks), so every value
+// is read once, every exponential is taken once and no barrier is needed.
 template <int NI>
 __global__ __launch_bounds__(256) void ipar_softmax_rows_kernel(Dims dm, ScoreArgs a) {
   const int wave = threadIdx.x / 64, lane = threadIdx.x % 64;
@@ -215,12 +182,15 @@ hipError_t launch_scores_t(const Dims& dm, const ScoreArgs& a, hipStream_t s) {
   hipLaunchKernelGGL((pooled_scores_kernel<D>), dim3((dm.m + 63) / 64, (dm.n + 63) / 64, bh), dim3(256), 0, s, dm, a);
   if (dm.tt > 0)
     hipLaunchKernelGGL((text_mass_kernel<D, BLK>), dim3((dm.n + 7) / 8, bh), dim3(256), 0, s, dm, a);
+  const dim3 rgrid((dm.n + 3) / 4, bh);
   if (dm.m <= 64 * 4)
-    hipLaunchKernelGGL(ipar_softmax_rows_kernel<4>, dim3((dm.n + 3) / 4, bh), dim3(256), 0, s, dm, a);
+    hipLaunchKernelGGL(ipar_softmax_rows_kernel<4>, rgrid, dim3(256), 0, s, dm, a);
   else if (dm.m <= 64 * 16)
-    hipLaunchKernelGGL(ipar_softmax_rows_kernel<16>, dim3((dm.n + 3) / 4, bh), dim3(256), 0, s, dm, a);
+    hipLaunchKernelGGL(ipar_softmax_rows_kernel<16>, rgrid, dim3(256), 0, s, dm, a);
+  else if (dm.m <= 64 * 32)
+    hipLaunchKernelGGL(ipar_softmax_rows_kernel<32>, rgrid, dim3(256), 0, s, dm, a);
   else
-    hipLaunchKernelGGL(ipar_softmax_kernel, dim3(dm.n, bh), dim3(256), 0, s, dm, a);
+    hipLaunchKernelGGL(ipar_softmax_rows_kernel<RSA_MAX_BLOCKS / 64>, rgrid, dim3(256), 0, s, dm, a);
   return hipGetLastError();
 }
 

@@ -2,17 +2,13 @@
 // Sec. 4.1 for R_n, Sec. 4.3 and the appendix "Implementations" for top-k and p).
 //
 // One wavefront per video query block. The row's M log-masses become order-preserving
-// 32-bit keys, lane l owning blocks l, l+64, ... (in registers for rows of at most 64 * NI
-// blocks, four rows per workgroup; in LDS for longer rows); the k-th largest key is found
+// 32-bit keys in registers, lane l owning blocks l, l+64, ... (four rows per workgroup, the
+// register count chosen by the row length); the k-th largest key is found
 // by a 32-step bitwise search whose counts are wave ballots, so the selection is exact
 // integer work (ties: lower block index first). The optional weight threshold p extends
 // the kept prefix, in the same descending order, until the kept A^pool exceeds p.
 // Outputs: mask bits, ascending block list, count, and R_n = sum of kept A^pool.
 #include "rsa_common.hpp"
-
-// The loops over a row's slots carry an unroll request for the register form (fixed trip count);
-// the LDS form has a run-time trip count, where the request cannot be met and the compiler says so.
-#pragma clang diagnostic ignored "-Wpass-failed"
 
 namespace rsa {
 namespace {
@@ -38,41 +34,29 @@ __device__ inline float wave_inclusive_scan(float v, int lane) {
   return v;
 }
 
-// NI > 0: keys and weights of a row in NI registers per lane, one row per wave of the workgroup.
-// NI == 0: in dynamic LDS, one row (one wave) per workgroup.
+// Keys and weights of a row in NI registers per lane (rows of up to 64 * NI blocks), one row per
+// wave of the workgroup.
 template <int NI>
-__global__ __launch_bounds__(NI > 0 ? 256 : 64) void select_kernel(Dims dm, SelectArgs a) {
-  extern __shared__ uint32_t smem[];
-  constexpr bool REG = NI > 0;
+__global__ __launch_bounds__(256) void select_kernel(Dims dm, SelectArgs a) {
   const int lane = threadIdx.x % 64;
-  const int n = REG ? blockIdx.x * 4 + (int)(threadIdx.x / 64) : blockIdx.x, bh = blockIdx.y;
+  const int n = blockIdx.x * 4 + (int)(threadIdx.x / 64), bh = blockIdx.y;
   if (n >= dm.n) return;                           // no barriers in this kernel
   const int M = dm.m;
-  const int slots = REG ? NI : (M + 63) / 64;
+  constexpr int slots = NI;
   const size_t row = (size_t)bh * dm.n + n;
   const float* L = a.Lmass + row * M;
   const float* A = a.Apool + row * M;
-  uint32_t rk[REG ? NI : 1];
-  float rv[REG ? NI : 1];
-  uint32_t* keys = smem;
-  float* vals = reinterpret_cast<float*>(smem + (REG ? 0 : slots * 64));
-  auto key_at = [&](int s) __attribute__((always_inline)) { return REG ? rk[REG ? s : 0] : keys[s * 64 + lane]; };
-  auto val_at = [&](int s) __attribute__((always_inline)) { return REG ? rv[REG ? s : 0] : vals[s * 64 + lane]; };
+  uint32_t rk[NI];
+  float rv[NI];
+  auto key_at = [&](int s) __attribute__((always_inline)) { return rk[s]; };
+  auto val_at = [&](int s) __attribute__((always_inline)) { return rv[s]; };
 
 #pragma unroll
   for (int s = 0; s < slots; ++s) {
     const int m = s * 64 + lane;
-    const uint32_t k = (m < M) ? orderable_key(L[m]) : 0u;   // 0 sorts below every real key
-    const float v = (m < M) ? A[m] : 0.f;
-    if (REG) {
-      rk[REG ? s : 0] = k;
-      rv[REG ? s : 0] = v;
-    } else {
-      keys[m] = k;
-      vals[m] = v;
-    }
+    rk[s] = (m < M) ? orderable_key(L[m]) : 0u;   // 0 sorts below every real key
+    rv[s] = (m < M) ? A[m] : 0.f;
   }
-  // (LDS form) every lane only ever reads back the entries it wrote: no barrier needed
 
   // k-th largest key
   uint32_t tau = 0;
@@ -156,16 +140,15 @@ __global__ __launch_bounds__(NI > 0 ? 256 : 64) void select_kernel(Dims dm, Sele
 }  // namespace
 
 hipError_t launch_select(const Dims& dm, const SelectArgs& a, hipStream_t s) {
-  const int bh = dm.batch * dm.heads;
-  if (dm.m <= 64 * 4) {
-    hipLaunchKernelGGL(select_kernel<4>, dim3((dm.n + 3) / 4, bh), dim3(256), 0, s, dm, a);
-  } else if (dm.m <= 64 * 16) {
-    hipLaunchKernelGGL(select_kernel<16>, dim3((dm.n + 3) / 4, bh), dim3(256), 0, s, dm, a);
-  } else {
-    const int slots = (dm.m + 63) / 64;
-    const size_t lds = (size_t)slots * 64 * 2 * sizeof(uint32_t);
-    hipLaunchKernelGGL(select_kernel<0>, dim3(dm.n, bh), dim3(64), lds, s, dm, a);
-  }
+  const dim3 grid((dm.n + 3) / 4, dm.batch * dm.heads), block(256);
+  if (dm.m <= 64 * 4)
+    hipLaunchKernelGGL(select_kernel<4>, grid, block, 0, s, dm, a);
+  else if (dm.m <= 64 * 16)
+    hipLaunchKernelGGL(select_kernel<16>, grid, block, 0, s, dm, a);
+  else if (dm.m <= 64 * 32)
+    hipLaunchKernelGGL(select_kernel<32>, grid, block, 0, s, dm, a);
+  else
+    hipLaunchKernelGGL(select_kernel<RSA_MAX_BLOCKS / 64>, grid, block, 0, s, dm, a);
   return hipGetLastError();
 }
 
