@@ -569,62 +569,70 @@ __global__ __launch_bounds__(2 * 64 * BLK / 32, 1) void attn_kernel(Dims dm, Att
 }
 
 // Pooled compensation (Alg. 1 step 21): C[n][:] = sum over blocks m that are not kept and
-// have their M_c bit set of A^pool[n][m] * v^pool[m][:], all fp32. A workgroup owns NQ = 16
-// query blocks and walks the key blocks in chunks of 512: first the chunk's weights
-// (A^pool where the block is compensated, else 0) go to LDS as one float4 per (group of four
-// query blocks, key block); then every thread accumulates one channel of 16*D/256 query
-// blocks, reading the weights as LDS broadcasts and v^pool straight from global memory
-// (coalesced, L2 resident, independent loads the compiler keeps in flight).
-constexpr int kCompNQ = 16, kCompMCH = 512;
-
+// have their M_c bit set of A^pool[n][m] * v^pool[m][:], all fp32, blocks in ascending order.
+// Most blocks are not compensated (the gate is off, or the block is kept), so the sum runs over
+// the set bits only. One wave per query block: lane l looks at block 64 s + l of slot s (its
+// bit, its weight: one coalesced read of the row of A^pool), a ballot gives the slot's
+// compensated blocks, and for each of them, eight at a time so that their loads are in flight
+// together, the weight is broadcast from its lane and the row of v^pool (L2 resident) is added,
+// every lane owning D/64 channels. Padding entries of a group of eight carry weight 0 and add
+// exactly nothing.
 template <int D>
 __global__ __launch_bounds__(256) void compensation_kernel(Dims dm, AttnArgs a) {
-  constexpr int NQ = kCompNQ, MCH = kCompMCH, NG = NQ / 4;
-  constexpr int RPT = NQ * D / 256;            // query blocks per thread (a multiple of 4)
-  __shared__ floatx4 wt4[NG * MCH];
-  const int bh = blockIdx.y, n0 = blockIdx.x * NQ;
-  const int tid = threadIdx.x;
-  const int dd = tid % D, g0 = (tid / D) * (RPT / 4);       // first weight group of this thread
-  float acc[RPT];
+  constexpr int CPL = D / 64;                    // channels per lane
+  constexpr int U = 8;                           // blocks per group
+  const int lane = threadIdx.x % 64;
+  const int n = blockIdx.x * 4 + (int)(threadIdx.x / 64), bh = blockIdx.y;
+  if (n >= dm.n) return;                         // no barriers in this kernel
+  const size_t row = (size_t)bh * dm.n + n;
+  const uint32_t* kept = a.mask_bits + row * dm.w;
+  const uint32_t* gate = a.Mc_bits + row * dm.w;
+  const float* A = a.Apool + row * dm.m;
+  const float* Vp = a.Vp + (size_t)bh * dm.m * D + lane;
+  float acc[CPL];
 #pragma unroll
-  for (int i = 0; i < RPT; ++i) acc[i] = 0.f;
-  const float* Vp = a.Vp + (size_t)bh * dm.m * D + dd;
-  for (int m0 = 0; m0 < dm.m; m0 += MCH) {
-    const int mc = dm.m - m0 < MCH ? dm.m - m0 : MCH;
-    for (int idx = tid; idx < NG * MCH; idx += 256) {
-      const int g = idx / MCH, mm = idx % MCH, m = m0 + mm;
-      floatx4 w = {0.f, 0.f, 0.f, 0.f};
-      if (mm < mc) {
-#pragma unroll
-        for (int e = 0; e < 4; ++e) {
-          const int n = n0 + 4 * g + e;
-          if (n < dm.n) {
-            const size_t row = (size_t)bh * dm.n + n;
-            const uint32_t bits = ~a.mask_bits[row * dm.w + m / 32] & a.Mc_bits[row * dm.w + m / 32];
-            if ((bits >> (m % 32)) & 1u) w[e] = a.Apool[row * dm.m + m];
-          }
-        }
-      }
-      wt4[idx] = w;
+  for (int c = 0; c < CPL; ++c) acc[c] = 0.f;
+  const int slots = (dm.m + 63) / 64;
+  // this lane's block of a slot: is it compensated, and its weight (read a slot ahead of its use)
+  auto look = [&](int s, bool& on, float& wl) __attribute__((always_inline)) {
+    const int m = 64 * s + lane, word = 2 * s + (lane >> 5);
+    on = false;
+    wl = 0.f;
+    if (m < dm.m) {
+      on = ((~kept[word] & gate[word]) >> (lane & 31)) & 1u;
+      if (on) wl = A[m];
     }
-    __syncthreads();
-#pragma unroll 8
-    for (int mm = 0; mm < mc; ++mm) {
-      const float v = Vp[(size_t)(m0 + mm) * D];
+  };
+  bool on_next;
+  float wl_next;
+  look(0, on_next, wl_next);
+  for (int s = 0; s < slots; ++s) {
+    const bool on = on_next;
+    const float wl = wl_next;
+    if (s + 1 < slots) look(s + 1, on_next, wl_next);
+    unsigned long long todo = __ballot(on);
+    while (todo) {
+      int src[U];
+      float wt[U];
 #pragma unroll
-      for (int q = 0; q < RPT / 4; ++q) {
-        const floatx4 w = wt4[(g0 + q) * MCH + mm];
-#pragma unroll
-        for (int e = 0; e < 4; ++e) acc[4 * q + e] = fmaf(w[e], v, acc[4 * q + e]);
+      for (int u = 0; u < U; ++u) {
+        src[u] = todo ? __builtin_ctzll(todo) : 0;           // wave-uniform
+        wt[u] = todo ? __shfl(wl, src[u]) : 0.f;
+        todo &= todo - 1;                                    // 0 stays 0
       }
+      float v[U][CPL];
+#pragma unroll
+      for (int u = 0; u < U; ++u)
+#pragma unroll
+        for (int c = 0; c < CPL; ++c) v[u][c] = Vp[(size_t)(64 * s + src[u]) * D + 64 * c];
+#pragma unroll
+      for (int u = 0; u < U; ++u)
+#pragma unroll
+        for (int c = 0; c < CPL; ++c) acc[c] = fmaf(wt[u], v[u][c], acc[c]);
     }
-    __syncthreads();
   }
 #pragma unroll
-  for (int i = 0; i < RPT; ++i) {
-    const int n = n0 + 4 * g0 + i;
-    if (n < dm.n) a.comp[((size_t)bh * dm.n + n) * D + dd] = acc[i];
-  }
+  for (int c = 0; c < CPL; ++c) a.comp[row * D + lane + 64 * c] = acc[c];
 }
 
 // Launch order of the video query blocks of one (batch, head): sorted by their first three
@@ -676,7 +684,7 @@ hipError_t launch_attn_t(const Dims& dm, const AttnArgs& a, hipStream_t s) {
   const long long grid = (long long)n_text_items + (dense_all ? 0 : (long long)bh * 8 * ((chunk + 1) / 2));
   if (grid <= 0 || grid > 0x7fffffffLL) return hipErrorInvalidValue;
   if (!dense_all && (a.flags & RSA_COMPENSATE))
-    hipLaunchKernelGGL((compensation_kernel<D>), dim3((dm.n + kCompNQ - 1) / kCompNQ, bh), dim3(256), 0, s, dm, a);
+    hipLaunchKernelGGL((compensation_kernel<D>), dim3((dm.n + 3) / 4, bh), dim3(256), 0, s, dm, a);
   if (!dense_all && a.row_order) hipLaunchKernelGGL(row_order_kernel, dim3(bh), dim3(1024), 0, s, dm, a);
   hipLaunchKernelGGL((attn_kernel<D, BLK>), dim3((unsigned)grid), dim3(C::NTHR), 0, s, dm, a, n_text_items, chunk);
   return hipGetLastError();
