@@ -1,8 +1,9 @@
 // Block-sparse flash attention with the rectification fused into the epilogue
 // (paper Sec. 3.1 sparse attention, Alg. 1 steps 16-17; Sec. 4.1 / 4.2, Alg. 1 steps 19-23).
 //
-// A workgroup owns two query blocks of one (batch, head): two groups of BLK/32 waves, one wave
-// per 32 query rows, wave w of either group on the same SIMD. Video query blocks walk their
+// A workgroup is eight waves and owns 256 query rows of one (batch, head): groups of BLK/32 waves,
+// one group per query block (two at BLK = 128, four at BLK = 64), one wave per 32 query rows,
+// groups g and g + NGRP/2 on the same SIMDs. Video query blocks walk their
 // compact, ascending list of critical key blocks; text query blocks (and every block under
 // RSA_DENSE) walk all M key blocks. Key blocks are consumed in steps of KVS keys. For each
 // step the K rows [KVS][d] and the channel-major V rows [d][KVS] of a group are brought into
@@ -45,7 +46,6 @@ typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));
 #ifndef RSA_NSTAGE
 #define RSA_NSTAGE 2
 #endif
-constexpr int KVS = RSA_KVS;        // keys per step
 constexpr int NSTAGE = RSA_NSTAGE;  // LDS ring depth per group
 #ifndef RSA_VPRE
 #define RSA_VPRE 4
@@ -58,8 +58,11 @@ constexpr int VPRE = RSA_VPRE;      // 16-key chunks of V^T operands fetched dur
 
 template <int D, int BLK>
 struct AttnCfg {
-  static constexpr int NW = BLK / 32;       // waves per workgroup (one per 32 query rows)
-  static constexpr int NTHR = 2 * 64 * NW;  // two groups of NW waves: two query blocks per workgroup
+  static constexpr int NW = BLK / 32;       // waves per group (one per 32 query rows)
+  static constexpr int NGRP = 8 / NW;       // groups = query blocks per workgroup: eight waves, two per SIMD
+  static constexpr int NTHR = 64 * NW * NGRP;
+  // keys per step; halved where four rings of 64 keys x 128 channels would not fit the LDS
+  static constexpr int KVS = (BLK == 64 && D == 128) ? RSA_KVS / 2 : RSA_KVS;
   static constexpr int SPB = BLK / KVS;     // steps per key block
   static constexpr int KT = KVS / 32;       // key tiles of S^T per step
   static constexpr int KS = D / 16;         // k-steps of K Q^T
@@ -75,7 +78,8 @@ struct AttnCfg {
   static constexpr int VBUF = D * VCPR;     // ... per V^T buffer
   static constexpr int STAGE = KBUF + VBUF; // one ring stage
   static_assert(KINST % NW == 0 && VINST % NW == 0, "loads must split evenly over the waves");
-  static_assert(NSTAGE == 2 && 2 * NSTAGE * STAGE * 16 <= 160 * 1024, "two rings of two stages must fit the LDS of a CU");
+  static_assert(NSTAGE == 2 && NGRP * NSTAGE * STAGE * 16 <= 160 * 1024, "the rings of all groups must fit the LDS of a CU");
+  static_assert(NGRP % 2 == 0 && BLK % KVS == 0, "groups pair up on the SIMDs; a block is a whole number of steps");
 };
 
 // LDS tiles are unpadded; the 16-byte chunk c of row r is stored at chunk position
@@ -116,38 +120,39 @@ template <int V>
 struct IntC { static constexpr int value = V; };
 
 template <int D, int BLK>
-__global__ __launch_bounds__(2 * 64 * BLK / 32, 1) void attn_kernel(Dims dm, AttnArgs a, int n_text_items,
+__global__ __launch_bounds__(512, 1) void attn_kernel(Dims dm, AttnArgs a, int n_text_items,
                                                                                   int chunk) {
   using C = AttnCfg<D, BLK>;
   constexpr int KBUF = C::KBUF;
-  __shared__ u32x4 lds_all[2 * NSTAGE * C::STAGE];   // per group a ring: stage st = [K rows | V^T rows]
+  constexpr int KVS = C::KVS, NGRP = C::NGRP;
+  __shared__ u32x4 lds_all[NGRP * NSTAGE * C::STAGE];   // per group a ring: stage st = [K rows | V^T rows]
 
   // ---- which (batch*head, query block) is this workgroup ---------------------------------
   const bool dense_all = (a.flags & RSA_DENSE) != 0;
   const int tid = threadIdx.x;
   const int wave_wg = __builtin_amdgcn_readfirstlane(tid / 64);
-  const int grp = wave_wg / C::NW;                   // which of the two query blocks of this workgroup
-  const int wave = wave_wg % C::NW;                  // wave inside the group (wave w of both groups shares a SIMD)
+  const int grp = wave_wg / C::NW;                   // which of the query blocks of this workgroup
+  const int wave = wave_wg % C::NW;                  // wave inside the group (groups g and g + NGRP/2 share their SIMDs)
   u32x4* lds = lds_all + grp * (NSTAGE * C::STAGE);
   int bh;
-  int qb_of[2];                                      // query block of either group, -1: none
+  int qb_of[NGRP];                                   // query block of every group, -1: none
   {
     const int id = blockIdx.x;
     if (id < n_text_items) {           // long dense rows first, two per workgroup
-      const int per = dense_all ? dm.m : dm.mt, pairs = (per + 1) / 2;
+      const int per = dense_all ? dm.m : dm.mt, pairs = (per + NGRP - 1) / NGRP;
       bh = id / pairs;
-      const int r0 = 2 * (id % pairs), first = dense_all ? 0 : dm.n;
-      qb_of[0] = first + r0;
-      qb_of[1] = r0 + 1 < per ? first + r0 + 1 : -1;
+      const int r0 = NGRP * (id % pairs), first = dense_all ? 0 : dm.n;
+#pragma unroll
+      for (int g = 0; g < NGRP; ++g) qb_of[g] = r0 + g < per ? first + r0 + g : -1;
     } else {
       const int v = id - n_text_items;
-      const int xcd = v & 7, j = v >> 3, pairs = (chunk + 1) / 2;
+      const int xcd = v & 7, j = v >> 3, pairs = (chunk + NGRP - 1) / NGRP;
       bh = j / pairs;
-      const int p0 = xcd * chunk + 2 * (j % pairs);                 // launch positions p0, p0 + 1
+      const int p0 = xcd * chunk + NGRP * (j % pairs);              // launch positions p0 .. p0 + NGRP - 1
       const int pend = min(dm.n, (xcd + 1) * chunk);
       if (p0 >= pend) return;          // whole workgroup leaves before any barrier
 #pragma unroll
-      for (int g = 0; g < 2; ++g) {
+      for (int g = 0; g < NGRP; ++g) {
         qb_of[g] = -1;
         if (p0 + g < pend) qb_of[g] = a.row_order ? a.row_order[(size_t)bh * dm.n + p0 + g] : p0 + g;
       }
@@ -158,7 +163,9 @@ __global__ __launch_bounds__(2 * 64 * BLK / 32, 1) void attn_kernel(Dims dm, Att
     const bool sp = !dense_all && qbx < dm.n;
     return (sp ? a.count[(size_t)bh * dm.n + qbx] : dm.m) * C::SPB;
   };
-  const int smax = max(steps_of(qb_of[0]), steps_of(qb_of[1]));   // both groups turn the loop this often
+  int smax = 0;                                      // every group turns the loop this often
+#pragma unroll
+  for (int g = 0; g < NGRP; ++g) smax = max(smax, steps_of(qb_of[g]));
   const int qb = qb_of[grp] < 0 ? 0 : qb_of[grp];
   const bool active = qb_of[grp] >= 0;
   const int b = bh / dm.heads, h = bh % dm.heads;
@@ -490,7 +497,7 @@ __global__ __launch_bounds__(2 * 64 * BLK / 32, 1) void attn_kernel(Dims dm, Att
   }
   __builtin_amdgcn_s_waitcnt(0x0070);
   group_barrier();                  // tile 0 of both groups is in LDS
-  if (grp == 1) group_barrier();    // group 1 runs one barrier behind group 0
+  if (grp >= NGRP / 2) group_barrier();    // the second half of the groups runs one barrier behind the first
   // Every group turns smax + 1 rounds of two barriers; a round is M(s), V(s) while the group has
   // steps left, the last P V product alone in round nsteps, and nothing but the barriers after.
   using Y = IntC<1>;
@@ -529,7 +536,7 @@ __global__ __launch_bounds__(2 * 64 * BLK / 32, 1) void attn_kernel(Dims dm, Att
     group_barrier();
     group_barrier();
   }
-  if (grp == 0) group_barrier();
+  if (grp < NGRP / 2) group_barrier();
 
   if (!active) return;      // no barrier follows
 
@@ -679,9 +686,10 @@ hipError_t launch_attn_t(const Dims& dm, const AttnArgs& a, hipStream_t s) {
   using C = AttnCfg<D, BLK>;
   const int bh = dm.batch * dm.heads;
   const bool dense_all = (a.flags & RSA_DENSE) != 0;
-  const int n_text_items = bh * (((dense_all ? dm.m : dm.mt) + 1) / 2);       // workgroups of dense rows, two rows each
+  constexpr int G = C::NGRP;                                                       // query blocks per workgroup
+  const int n_text_items = bh * (((dense_all ? dm.m : dm.mt) + G - 1) / G);       // workgroups of dense rows
   const int chunk = (dm.n + 7) / 8;
-  const long long grid = (long long)n_text_items + (dense_all ? 0 : (long long)bh * 8 * ((chunk + 1) / 2));
+  const long long grid = (long long)n_text_items + (dense_all ? 0 : (long long)bh * 8 * ((chunk + G - 1) / G));
   if (grid <= 0 || grid > 0x7fffffffLL) return hipErrorInvalidValue;
   if (!dense_all && (a.flags & RSA_COMPENSATE))
     hipLaunchKernelGGL((compensation_kernel<D>), dim3((dm.n + 3) / 4, bh), dim3(256), 0, s, dm, a);
