@@ -47,14 +47,10 @@ typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));
 #define RSA_NSTAGE 2
 #endif
 constexpr int NSTAGE = RSA_NSTAGE;  // LDS ring depth per group
-#ifndef RSA_VPRE
-#define RSA_VPRE 4
-#endif
 #ifndef RSA_MWIN
 #define RSA_MWIN 8
 #endif
 constexpr int MWIN = RSA_MWIN;      // MFMA slots between the LDS read of a K operand and its use
-constexpr int VPRE = RSA_VPRE;      // 16-key chunks of V^T operands fetched during the softmax (the rest: at the start of the MFMA phase)
 
 template <int D, int BLK>
 struct AttnCfg {
@@ -344,7 +340,7 @@ __global__ __launch_bounds__(512, 1) void attn_kernel(Dims dm, AttnArgs a, int n
   }
 
   // M(s) as one fixed sequence of NPV + NQK MFMA slots: the P V product of step s-1 (operands in
-  // registers, except the last chunks, read at the start), then K Q^T of step s. The K operand of
+  // registers), then K Q^T of step s. The K operand of
   // slot i is read from LDS W slots ahead of its MFMA into a ring of W registers, so LDS latency
   // stays behind MFMAs that already have their operands; the order is pinned slot by slot.
   auto m_phase = [&](auto stc, auto pvc, auto qkc, int s) __attribute__((always_inline)) {
@@ -352,7 +348,7 @@ __global__ __launch_bounds__(512, 1) void attn_kernel(Dims dm, AttnArgs a, int n
     constexpr bool do_pv = decltype(pvc)::value != 0, do_qk = decltype(qkc)::value != 0;
     constexpr int NPV = C::PC * C::DT, NQK = C::KS * C::KT, NSLOT = NPV + NQK;
     constexpr int W = MWIN;
-    constexpr int DSLOT = (VPRE < C::PC) ? (C::DT < NPV ? C::DT : 1) : 1;     // where the next tile is requested
+    constexpr int DSLOT = 1;                          // the slot in which the requests for the next tile start
     const bool more = s + 1 < nsteps;
     Tile nt = {};
     bool full = true;
@@ -361,13 +357,6 @@ __global__ __launch_bounds__(512, 1) void attn_kernel(Dims dm, AttnArgs a, int n
       const int q = slot - NPV, k2 = q / C::KT, t = q % C::KT;
       kring[slot % W] = __builtin_bit_cast(bf16x8, kread[k2][ST * C::STAGE + t * 32 * C::KCPR]);
     };
-    if (do_pv) {
-#pragma unroll
-      for (int pc = VPRE; pc < C::PC; ++pc)
-#pragma unroll
-        for (int dt = 0; dt < C::DT; ++dt)
-          vop[pc][dt] = __builtin_bit_cast(bf16x8, vread[pc][(1 - ST) * C::STAGE + dt * 32 * C::VCPR]);
-    }
     if (do_qk) {
 #pragma unroll
       for (int j = NPV; j < W && j < NSLOT; ++j) read_k(j);
@@ -375,7 +364,6 @@ __global__ __launch_bounds__(512, 1) void attn_kernel(Dims dm, AttnArgs a, int n
     __builtin_amdgcn_sched_barrier(0);
 #pragma unroll
     for (int i = 0; i < NSLOT; ++i) {
-      if (i == DSLOT && DSLOT > 1) __builtin_amdgcn_s_waitcnt(0xC07F);      // lgkmcnt(0): stage 1-ST is free
       // one load of the tile of step s+1 per slot, behind the MFMA of the slot before
       if (i == DSLOT && more && !full) issue_ragged(nt);
       if (i >= DSLOT && i - DSLOT < LPS) {
@@ -414,7 +402,7 @@ __global__ __launch_bounds__(512, 1) void attn_kernel(Dims dm, AttnArgs a, int n
     constexpr int ST = decltype(stc)::value;
     {
 #pragma unroll
-      for (int pc = 0; pc < VPRE; ++pc)
+      for (int pc = 0; pc < C::PC; ++pc)
 #pragma unroll
         for (int dt = 0; dt < C::DT; ++dt)
           vop[pc][dt] = __builtin_bit_cast(bf16x8, vread[pc][ST * C::STAGE + dt * 32 * C::VCPR]);
