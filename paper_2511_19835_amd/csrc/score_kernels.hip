@@ -30,19 +30,35 @@ __device__ inline float wave_sum(float v) {
 // sums, so the scores keep full single precision (the selection that follows is compared with
 // fp64 inside a 1e-4 band). The contraction index may be visited in any order as long as both
 // operands agree: k-step s takes channel s from the lanes of the lower half-wave and channel
-// D/2 + s from the upper one, so every lane reads D/2 consecutive floats of its row.
+// D/2 + s from the upper one, so every lane needs D/2 consecutive floats of its row.
+// The 64 query rows and 64 key rows of a workgroup come in through LDS: read from global memory
+// with every wave load covering two whole rows (a lane reading its own row directly touches 64
+// cache lines per load and the kernel is then bound by the address unit of the CU), then read
+// back per lane; a row stride of D + 4 floats keeps the 16-byte LDS reads free of bank conflicts.
 template <int D>
 __global__ __launch_bounds__(256) void pooled_scores_kernel(Dims dm, ScoreArgs a) {
   constexpr int KH = D / 2;                     // k-steps; channels per half-wave
+  constexpr int RS = D + 4;                     // LDS row stride in floats
+  constexpr int C4 = D / 4;                     // float4 per row
+  __shared__ float rows[2][64 * RS];            // [0]: pooled queries n0 .. n0+63, [1]: pooled keys m0 .. m0+63
   const int bh = blockIdx.z;
   const int wave = threadIdx.x / 64, lane = threadIdx.x % 64;
   const int l32 = lane % 32, hf = lane / 32;
-  const int n0 = blockIdx.y * 64 + (wave / 2) * 32, m0 = blockIdx.x * 64 + (wave % 2) * 32;
-  if (n0 >= dm.n || m0 >= dm.m) return;         // no barriers in this kernel
-  const int n = n0 + l32 < dm.n ? n0 + l32 : dm.n - 1;        // rows past the end repeat the last one (not stored)
-  const int m = m0 + l32 < dm.m ? m0 + l32 : dm.m - 1;
-  const floatx4* qrow = reinterpret_cast<const floatx4*>(a.Qp + ((size_t)bh * dm.n + n) * D + hf * KH);
-  const floatx4* krow = reinterpret_cast<const floatx4*>(a.Kp + ((size_t)bh * dm.m + m) * D + hf * KH);
+  const int nb = blockIdx.y * 64, mb = blockIdx.x * 64;
+  for (int idx = threadIdx.x; idx < 64 * C4; idx += 256) {
+    const int r = idx / C4, c4 = idx % C4;
+    const int n = nb + r < dm.n ? nb + r : dm.n - 1;          // rows past the end repeat the last one (not stored)
+    const int m = mb + r < dm.m ? mb + r : dm.m - 1;
+    *reinterpret_cast<floatx4*>(&rows[0][r * RS + 4 * c4]) =
+        *reinterpret_cast<const floatx4*>(a.Qp + ((size_t)bh * dm.n + n) * D + 4 * c4);
+    *reinterpret_cast<floatx4*>(&rows[1][r * RS + 4 * c4]) =
+        *reinterpret_cast<const floatx4*>(a.Kp + ((size_t)bh * dm.m + m) * D + 4 * c4);
+  }
+  __syncthreads();
+  const int n0 = nb + (wave / 2) * 32, m0 = mb + (wave % 2) * 32;
+  if (n0 >= dm.n || m0 >= dm.m) return;         // after the only barrier
+  const floatx4* qrow = reinterpret_cast<const floatx4*>(&rows[0][((wave / 2) * 32 + l32) * RS + hf * KH]);
+  const floatx4* krow = reinterpret_cast<const floatx4*>(&rows[1][((wave % 2) * 32 + l32) * RS + hf * KH]);
   floatx4 qv[KH / 4], kv[KH / 4];
 #pragma unroll
   for (int i = 0; i < KH / 4; ++i) {
