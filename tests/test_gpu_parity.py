@@ -45,7 +45,7 @@ def _run_and_compare(harness, cfg, seed=0, heads=None, layout="bhtd", **kw):
 
 
 def test_tiny_config_full_parity(gpu):
-    """BASELINE config 0: 2 heads, d 64, 1024 video + 64 text tokens, block 64, 75 % sparsity."""
+    """The small benchmark configuration: 2 heads, d 64, 1024 video + 64 text tokens, block 64, 75 % sparsity."""
     import parity
     from oracle import rsa_oracle as ro
     cfg = synth.CONFIGS["tiny"]
@@ -69,7 +69,7 @@ def test_tiny_config_full_parity(gpu):
 
 
 def test_mid_config_two_heads_parity(gpu):
-    """BASELINE config 1 shape (20 280 video tokens, ragged last block, block 128, d 128, 90 %)."""
+    """The mid-size benchmark shape (20 280 video tokens, ragged last block, block 128, d 128, 90 %)."""
     cfg = synth.CONFIGS["mid"]
     out, stats, _ = _run_and_compare(gpu, cfg, heads=[0, 7])
     assert (out["count"] == 16).all()
@@ -235,7 +235,7 @@ def test_results_are_deterministic(gpu):
 
 
 def test_full_size_hunyuan_shape_sampled(gpu):
-    """BASELINE config 3 at full size (24 heads, 118 800 video + 256 text tokens, block 128,
+    """The headline benchmark configuration at full size (24 heads, 118 800 video + 256 text tokens, block 128,
     90 %), in the launch configuration the benchmark times. All pooled tensors, masks, gates
     and factors of two heads are compared in full; outputs on sampled query blocks (first,
     ragged last video block, both text blocks, 12 random); cheap properties on every head."""
@@ -333,7 +333,7 @@ def _sampled_shape_check(gpu, cfg, heads, seed, sparsity, n_random=8, **kw):
 
 
 def test_wan_shape_sampled(gpu):
-    """BASELINE config 2 (Wan-2.1-like: 21x45x80 = 75 600 video tokens, no text, block 128, 90 %),
+    """The second full-size benchmark configuration (Wan-2.1-like: 21x45x80 = 75 600 video tokens, no text, block 128, 90 %),
     three of its 40 heads."""
     cfg = synth.CONFIGS["wan"]
     out = _sampled_shape_check(gpu, cfg, [0, 19, 39], 0, cfg.sparsity)
@@ -342,7 +342,7 @@ def test_wan_shape_sampled(gpu):
 
 @pytest.mark.parametrize("sparsity,seed,head", [(0.0, 0, 2), (0.5, 1, 5), (0.75, 2, 7), (0.85, 1, 11), (0.95, 2, 23)])
 def test_sparsity_sweep_at_hunyuan_shape(gpu, sparsity, seed, head):
-    """BASELINE config 4: the sparsity sweep at the config-3 shape (one head per point, seeds 0-2).
+    """The sparsity sweep at the headline shape (one head per point, seeds 0-2).
     At sparsity 0 every block is critical: R = 1, nothing is compensated, output = dense attention."""
     cfg = synth.CONFIGS["hunyuan"]
     out = _sampled_shape_check(gpu, cfg, [head], seed, sparsity, n_random=4 if sparsity < 0.7 else 8)
