@@ -1,5 +1,7 @@
 """GPU parity: the HIP path behind the C-ABI against the CPU oracle, element by element,
 on the same seeded inputs. Needs an MI355X: run with ``-m gpu``."""
+import os
+
 import numpy as np
 import pytest
 
@@ -73,6 +75,47 @@ def test_mid_config_two_heads_parity(gpu):
     cfg = synth.CONFIGS["mid"]
     out, stats, _ = _run_and_compare(gpu, cfg, heads=[0, 7])
     assert (out["count"] == 16).all()
+
+
+def _random_config(rng, i):
+    d = int(rng.choice([64, 128]))
+    block = int(rng.choice([64, 128]))
+    grid = (int(rng.integers(1, 6)), int(rng.integers(3, 14)), int(rng.integers(3, 18)))
+    t_text = int(rng.choice([0, 0, 1, 17, 64, 130, 257]))
+    heads = int(rng.integers(1, 4))
+    sparsity = float(rng.choice([0.3, 0.5, 0.7, 0.9]))
+    return LayerConfig(f"random{i}", 1, heads, d, grid, t_text, block, sparsity)
+
+
+@pytest.mark.parametrize("case", range(int(os.environ.get("RSA_RANDOM_CASES", "16"))))
+def test_random_shapes(gpu, case):
+    """Seeded random shapes over both head dimensions and block sizes, ragged grids, odd text
+    lengths, with the weight threshold and the rectification flags drawn at random too."""
+    rng = np.random.default_rng(1000 + case)
+    cfg = _random_config(rng, case)
+    p = float(rng.choice([0.0, 0.0, 0.2, 0.4]))
+    flags = int(rng.choice([3, 3, 1, 2, 0]))
+    gapr_mode = int(rng.choice([1, 1, 0, 2]))
+    print(f"  {cfg} p={p} flags={flags} gapr_mode={gapr_mode}", flush=True)
+    if p > 0.0:
+        # the extension decides on cumulative fp32 sums: compare outputs on the GPU's own masks
+        import parity
+        Qb, Kb, Vb = synth.make_inputs(cfg, 2000 + case)
+        out = gpu.run_layer(Qb, Kb, Vb, cfg.t_video, cfg.t_text, cfg.block, cfg.sparsity, p=p, gapr_mode=gapr_mode, flags=flags)
+        for h in range(cfg.heads):
+            ref = parity.oracle_head(Qb[0, h], Kb[0, h], Vb[0, h], cfg.t_video, cfg.t_text, cfg.block, cfg.sparsity,
+                                     p=p, gapr_mode=gapr_mode, rectify=bool(flags & 1), compensate=bool(flags & 2))
+            A = ref["A_pool"]
+            cs = np.cumsum(-np.sort(-A, axis=1), axis=1)
+            clear = np.abs(cs - p).min(axis=1) > 1e-5
+            np.testing.assert_array_equal(out["mask"][0, h][clear], ref["mask"][clear])
+            gm = out["mask"][0, h].copy()
+            O = _oracle_output_with_mask(ref, gm, Qb[0, h], Kb[0, h], Vb[0, h], rectify=bool(flags & 1),
+                                         compensate=bool(flags & 2))
+            parity.compare_head(out, 0, h, dict(ref, mask=gm, R=(A * gm).sum(axis=1), O=O), Qb[0, h], Kb[0, h], Vb[0, h],
+                                p=p, rectify=bool(flags & 1), compensate=bool(flags & 2))
+    else:
+        _run_and_compare(gpu, cfg, seed=2000 + case, p=p, flags=flags, gapr_mode=gapr_mode)
 
 
 def test_peaky_inputs_parity(gpu):
@@ -190,15 +233,17 @@ def test_weight_threshold_extension(gpu):
     assert extended > 0, "the threshold never extended a row: the case proves nothing"
 
 
-def _oracle_output_with_mask(ref, mask, Qb, Kb, Vb):
+def _oracle_output_with_mask(ref, mask, Qb, Kb, Vb, rectify=True, compensate=True):
     from oracle import rsa_oracle as ro
     Q, K, V = (ro.bf16_bits_to_f64(x) for x in (Qb, Kb, Vb))
     part = ref["part"]
     O = ref["O"].copy()
-    R = (ref["A_pool"] * mask).sum(axis=1)
+    R = (ref["A_pool"] * mask).sum(axis=1) if rectify else np.ones(part.n_video)
     C = ro.compensation(ref["A_pool"], mask, ref["Mc"], ref["Vp"])
     for n in range(part.n_video):
-        O[part.tokens(n)] = ro.sparse_attention_block(Q, K, V, mask[n], n, part, ref["scale"]) * R[n] + C[n][None, :]
+        O[part.tokens(n)] = ro.sparse_attention_block(Q, K, V, mask[n], n, part, ref["scale"]) * R[n]
+        if compensate:
+            O[part.tokens(n)] += C[n][None, :]
     return O
 
 
