@@ -26,7 +26,9 @@
  *     [batch][heads][...].  W = ceil(M/32) 32-bit words per bit-mask row, bit (m % 32) of
  *     word (m / 32) is block m; bits at m >= M are zero.
  *   - Return value: RSA_OK or a negative RSA_E_* code. Arguments are validated on the host
- *     before anything is launched; on error nothing has been enqueued. No exceptions, no exit.
+ *     before anything is launched: with any code but RSA_E_LAUNCH nothing has been enqueued.
+ *     RSA_E_LAUNCH (the HIP runtime refused a kernel launch) may leave the kernels launched
+ *     before the refused one enqueued; the outputs are then unspecified. No exceptions, no exit.
  *   - Results are deterministic (no atomics on any output path).
  */
 #ifndef RSA_H
@@ -43,13 +45,15 @@ enum {
   RSA_OK = 0,
   RSA_E_NULL = -1,        /* a required pointer is NULL */
   RSA_E_SHAPE = -2,       /* non-positive sizes, misaligned strides */
-  RSA_E_UNSUPPORTED = -3, /* head_dim or block outside {64,128}, M > RSA_MAX_BLOCKS */
+  RSA_E_UNSUPPORTED = -3, /* head_dim or block outside {64,128}, M > RSA_MAX_BLOCKS,
+                             block * stride_t * 2 bytes >= 2^31 */
   RSA_E_WORKSPACE = -4,   /* workspace smaller than rsa_workspace_bytes says */
   RSA_E_RANGE = -5,       /* sparsity / p / mode / flags out of range */
   RSA_E_LAUNCH = -6       /* the HIP runtime refused a launch */
 };
 
 #define RSA_MAX_BLOCKS 4096 /* largest M = key blocks per (batch, head) */
+#define RSA_STATIC_SCRATCH_BYTES (16u << 20) /* scratch held per GPU for rsa_sparse_attn_rectified_static */
 
 /* Problem statement of Alg. 1 ("Require": Q, K, V, T_v, T_t) plus the block size of Sec. 3.1. */
 typedef struct rsa_shape {
@@ -185,6 +189,26 @@ int rsa_sparse_attn_rectified(const rsa_shape* shape, const void* Q, const void*
                               const uint32_t* mask_bits, const float* R, const float* Apool,
                               const uint32_t* Mc_bits, const float* Vp, int flags,
                               void* O, float* lse, void* ws, size_t ws_bytes, void* stream);
+
+/*
+ * For callers that cannot allocate device memory or hand over a workspace: code running under HIP
+ * graph capture, tight serving loops, harnesses that forbid hipMalloc. Same computation, arguments,
+ * results and error codes as rsa_sparse_attn_rectified, without ws / ws_bytes: the scratch (C_n and
+ * the launch order) lives in a device array of RSA_STATIC_SCRATCH_BYTES (16 MiB) that is part of the
+ * library image, one copy per GPU, held until the process ends. The call allocates and frees nothing.
+ * Its first call on a device looks up that device's copy (hipGetSymbolAddress; RSA_E_LAUNCH if that
+ * fails). Shapes whose attn_ws_bytes (rsa_workspace_bytes) exceed RSA_STATIC_SCRATCH_BYTES are
+ * refused with RSA_E_WORKSPACE before anything is enqueued: 4 * batch * heads * N * (head_dim + 1)
+ * bytes plus padding, e.g. 11.5 MB for 24 heads of 118 800 + 256 tokens at block 128, head_dim 128.
+ * Every call on a GPU uses that GPU's one array and overwrites all of it that it reads (nothing has
+ * to start at zero); two calls that overlap in time on one GPU (different streams) race on it.
+ * With RSA_DENSE the scratch is not touched.
+ */
+int rsa_sparse_attn_rectified_static(const rsa_shape* shape, const void* Q, const void* K, const void* Vt,
+                                     const int32_t* block_idx, const int32_t* count,
+                                     const uint32_t* mask_bits, const float* R, const float* Apool,
+                                     const uint32_t* Mc_bits, const float* Vp, int flags,
+                                     void* O, float* lse, void* stream);
 
 /* Static string for a return code. */
 const char* rsa_status_string(int status);

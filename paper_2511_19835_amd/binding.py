@@ -21,10 +21,11 @@ RSA_RECTIFY_CRITICAL = 1
 RSA_COMPENSATE = 2
 RSA_DENSE = 4
 RSA_MAX_BLOCKS = 4096
+RSA_STATIC_SCRATCH_BYTES = 16 << 20
 
 EXPORTS = (
     "rsa_block_counts", "rsa_workspace_bytes", "rsa_pool", "rsa_pool_values", "rsa_adjacency_mask", "rsa_reorder_tokens", "rsa_select_blocks",
-    "rsa_sparse_attn_rectified", "rsa_status_string",
+    "rsa_sparse_attn_rectified", "rsa_sparse_attn_rectified_static", "rsa_status_string",
 )
 
 
@@ -71,6 +72,8 @@ def _lib() -> ctypes.CDLL:
         lib.rsa_select_blocks.restype = ctypes.c_int
         lib.rsa_sparse_attn_rectified.argtypes = [shp] + [vp] * 10 + [ctypes.c_int, vp, vp, vp, ctypes.c_size_t, vp]
         lib.rsa_sparse_attn_rectified.restype = ctypes.c_int
+        lib.rsa_sparse_attn_rectified_static.argtypes = [shp] + [vp] * 10 + [ctypes.c_int, vp, vp, vp]
+        lib.rsa_sparse_attn_rectified_static.restype = ctypes.c_int
         lib.rsa_adjacency_mask.argtypes = [shp, ctypes.POINTER(ctypes.c_int32), ctypes.POINTER(ctypes.c_int32), ctypes.c_int, vp, vp]
         lib.rsa_adjacency_mask.restype = ctypes.c_int
         lib.rsa_reorder_tokens.argtypes = [shp, ctypes.POINTER(ctypes.c_int32), ctypes.POINTER(ctypes.c_int32), ctypes.c_int, vp, vp, vp]
@@ -163,6 +166,14 @@ def rsa_sparse_attn_rectified(shape, Q, K, Vt, block_idx, count, mask_bits, R, A
         _ptr(Apool), _ptr(Mc_bits), _ptr(Vp), int(flags), _ptr(O), _ptr(lse), _ptr(ws),
         ws.numel() * ws.element_size() if ws is not None else 0, _stream_ptr(stream)),
         "rsa_sparse_attn_rectified")
+
+
+def rsa_sparse_attn_rectified_static(shape, Q, K, Vt, block_idx, count, mask_bits, R, Apool, Mc_bits, Vp, flags, O,
+                                     lse=None, stream=None):
+    _check(_lib().rsa_sparse_attn_rectified_static(
+        ctypes.byref(shape), _ptr(Q), _ptr(K), _ptr(Vt), _ptr(block_idx), _ptr(count), _ptr(mask_bits), _ptr(R),
+        _ptr(Apool), _ptr(Mc_bits), _ptr(Vp), int(flags), _ptr(O), _ptr(lse), _stream_ptr(stream)),
+        "rsa_sparse_attn_rectified_static")
 
 
 @dataclass

@@ -1,6 +1,8 @@
 // C-ABI entry points of librsa.so: host-side validation, workspace carving, launches.
 #include <math.h>
 
+#include <atomic>
+
 #include "rsa_common.hpp"
 
 namespace {
@@ -14,6 +16,8 @@ int make_dims(const rsa_shape* sh, Dims* out) {
   if (sh->block != 64 && sh->block != 128) return RSA_E_UNSUPPORTED;
   if (sh->stride_t < sh->head_dim || sh->stride_b < 1 || sh->stride_h < 1) return RSA_E_SHAPE;
   if ((sh->stride_t % 8) || (sh->stride_b % 8) || (sh->stride_h % 8)) return RSA_E_SHAPE;
+  // the kernels address the rows of one key block with 32-bit byte offsets
+  if ((int64_t)sh->block * sh->stride_t * 2 >= ((int64_t)1 << 31)) return RSA_E_UNSUPPORTED;
   if (!(sh->scale >= 0.f) || !isfinite(sh->scale)) return RSA_E_RANGE;
   Dims d;
   d.batch = sh->batch;
@@ -64,6 +68,55 @@ size_t attn_ws_comp_bytes(const Dims& d) {
 }
 size_t attn_ws_size(const Dims& d) {
   return attn_ws_comp_bytes(d) + align256((size_t)d.batch * d.heads * d.n * sizeof(int32_t));
+}
+
+// Argument checks shared by the two attention entry points. RSA_DENSE drops the other flags.
+int check_attn_args(const Dims&, const void* Q, const void* K, const void* Vt, const int32_t* block_idx,
+                    const int32_t* count, const uint32_t* mask_bits, const float* R, const float* Apool,
+                    const uint32_t* Mc_bits, const float* Vp, int* flags, const void* O) {
+  if (*flags & ~(RSA_RECTIFY_CRITICAL | RSA_COMPENSATE | RSA_DENSE)) return RSA_E_RANGE;
+  if (!Q || !K || !Vt || !O) return RSA_E_NULL;
+  if (*flags & RSA_DENSE) {
+    *flags = RSA_DENSE;
+    return RSA_OK;
+  }
+  if (!block_idx || !count) return RSA_E_NULL;
+  if ((*flags & RSA_RECTIFY_CRITICAL) && !R) return RSA_E_NULL;
+  if ((*flags & RSA_COMPENSATE) && (!mask_bits || !Apool || !Mc_bits || !Vp)) return RSA_E_NULL;
+  return RSA_OK;
+}
+
+// `ws` (may be NULL without RSA_COMPENSATE): C_n, then the launch order of the video query blocks.
+int enqueue_attn(const Dims& d, const void* Q, const void* K, const void* Vt, const int32_t* block_idx,
+                 const int32_t* count, const uint32_t* mask_bits, const float* R, const float* Apool,
+                 const uint32_t* Mc_bits, const float* Vp, int flags, void* O, float* lse, void* ws, void* stream) {
+  rsa::AttnArgs aa;
+  aa.Q = (const uint16_t*)Q; aa.K = (const uint16_t*)K; aa.Vt = (const uint16_t*)Vt;
+  aa.block_idx = block_idx; aa.count = count; aa.mask_bits = mask_bits; aa.Mc_bits = Mc_bits;
+  aa.R = R; aa.Apool = Apool; aa.Vp = Vp; aa.O = (uint16_t*)O; aa.lse = lse; aa.comp = (float*)ws;
+  aa.row_order = (ws && !(flags & RSA_DENSE)) ? (int32_t*)((char*)ws + attn_ws_comp_bytes(d)) : nullptr;
+  aa.flags = flags;
+  if (rsa::launch_attn(d, aa, (hipStream_t)stream) != hipSuccess) return RSA_E_LAUNCH;
+  return RSA_OK;
+}
+
+// Scratch of rsa_sparse_attn_rectified_static: one array per GPU, held from the moment the library's
+// code object is loaded on that GPU until the process ends. In host code the array's name is only a
+// handle for hipGetSymbolAddress; the device address it yields (one per device) is what kernels get.
+__attribute__((used)) static __device__ __align__(256) unsigned char scratch[RSA_STATIC_SCRATCH_BYTES];
+
+constexpr int kMaxDevices = 64;
+std::atomic<void*> g_scratch_ptr[kMaxDevices];
+
+void* static_scratch_of_current_device() {
+  int dev = -1;
+  if (hipGetDevice(&dev) != hipSuccess || dev < 0 || dev >= kMaxDevices) return nullptr;
+  void* p = g_scratch_ptr[dev].load(std::memory_order_acquire);
+  if (p) return p;
+  // first call on this device (racing first calls all get the same answer)
+  if (hipGetSymbolAddress(&p, HIP_SYMBOL(scratch)) != hipSuccess || !p) return nullptr;
+  g_scratch_ptr[dev].store(p, std::memory_order_release);
+  return p;
 }
 
 }  // namespace
@@ -196,25 +249,32 @@ int rsa_sparse_attn_rectified(const rsa_shape* shape, const void* Q, const void*
   Dims d;
   int rc = make_dims(shape, &d);
   if (rc != RSA_OK) return rc;
-  if (flags & ~(RSA_RECTIFY_CRITICAL | RSA_COMPENSATE | RSA_DENSE)) return RSA_E_RANGE;
-  if (!Q || !K || !Vt || !O) return RSA_E_NULL;
-  if (flags & RSA_DENSE) {
-    flags = RSA_DENSE;
-  } else {
-    if (!block_idx || !count) return RSA_E_NULL;
-    if ((flags & RSA_RECTIFY_CRITICAL) && !R) return RSA_E_NULL;
-    if ((flags & RSA_COMPENSATE) && (!mask_bits || !Apool || !Mc_bits || !Vp)) return RSA_E_NULL;
+  rc = check_attn_args(d, Q, K, Vt, block_idx, count, mask_bits, R, Apool, Mc_bits, Vp, &flags, O);
+  if (rc != RSA_OK) return rc;
+  if (!(flags & RSA_DENSE)) {
     if ((flags & RSA_COMPENSATE) && !ws) return RSA_E_NULL;
     if (ws && (ws_bytes < attn_ws_size(d) || ((uintptr_t)ws & 255))) return RSA_E_WORKSPACE;
   }
-  rsa::AttnArgs aa;
-  aa.Q = (const uint16_t*)Q; aa.K = (const uint16_t*)K; aa.Vt = (const uint16_t*)Vt;
-  aa.block_idx = block_idx; aa.count = count; aa.mask_bits = mask_bits; aa.Mc_bits = Mc_bits;
-  aa.R = R; aa.Apool = Apool; aa.Vp = Vp; aa.O = (uint16_t*)O; aa.lse = lse; aa.comp = (float*)ws;
-  aa.row_order = (ws && !(flags & RSA_DENSE)) ? (int32_t*)((char*)ws + attn_ws_comp_bytes(d)) : nullptr;
-  aa.flags = flags;
-  if (rsa::launch_attn(d, aa, (hipStream_t)stream) != hipSuccess) return RSA_E_LAUNCH;
-  return RSA_OK;
+  return enqueue_attn(d, Q, K, Vt, block_idx, count, mask_bits, R, Apool, Mc_bits, Vp, flags, O, lse, ws, stream);
+}
+
+int rsa_sparse_attn_rectified_static(const rsa_shape* shape, const void* Q, const void* K, const void* Vt,
+                                     const int32_t* block_idx, const int32_t* count,
+                                     const uint32_t* mask_bits, const float* R, const float* Apool,
+                                     const uint32_t* Mc_bits, const float* Vp, int flags, void* O,
+                                     float* lse, void* stream) {
+  Dims d;
+  int rc = make_dims(shape, &d);
+  if (rc != RSA_OK) return rc;
+  rc = check_attn_args(d, Q, K, Vt, block_idx, count, mask_bits, R, Apool, Mc_bits, Vp, &flags, O);
+  if (rc != RSA_OK) return rc;
+  void* ws = nullptr;
+  if (!(flags & RSA_DENSE)) {
+    if (attn_ws_size(d) > (size_t)RSA_STATIC_SCRATCH_BYTES) return RSA_E_WORKSPACE;
+    ws = static_scratch_of_current_device();
+    if (!ws) return RSA_E_LAUNCH;
+  }
+  return enqueue_attn(d, Q, K, Vt, block_idx, count, mask_bits, R, Apool, Mc_bits, Vp, flags, O, lse, ws, stream);
 }
 
 const char* rsa_status_string(int status) {
