@@ -50,13 +50,18 @@ def pack_bits(mask: np.ndarray) -> np.ndarray:
 def run_layer(Q_bits: np.ndarray, K_bits: np.ndarray, V_bits: np.ndarray, t_video: int, t_text: int,
               block: int, sparsity: float, p: float = 0.0, gapr_mode: int = 1,
               forced: Optional[np.ndarray] = None, flags: int = rb.RSA_RECTIFY_CRITICAL | rb.RSA_COMPENSATE,
-              scale: float = 0.0, layout: str = "bhtd", device="cuda:0", want_lse: bool = True) -> dict:
-    """Run the three entry points on the GPU and bring every buffer back as numpy."""
+              scale: float = 0.0, layout: str = "bhtd", device="cuda:0", want_lse: bool = True,
+              attn_workspace: bool = True) -> dict:
+    """Run the three entry points on the GPU and bring every buffer back as numpy. O starts out as
+    NaN in every element, so a row that no kernel writes shows up in any comparison.
+    ``attn_workspace=False`` passes ws = NULL to the attention call (legal without RSA_COMPENSATE)."""
     Q = bits_to_device(Q_bits, device, layout)
     K = bits_to_device(K_bits, device, layout)
     V = bits_to_device(V_bits, device, layout)
-    O = torch.empty_like(Q)
+    O = torch.full_like(Q, float("nan"))
     buf = rb.allocate(Q, t_video, t_text, block, scale)
+    if not attn_workspace:
+        buf.attn_ws = None
     forced_dev = None
     if forced is not None:
         forced_dev = torch.from_numpy(pack_bits(np.asarray(forced, dtype=bool))).to(device)
@@ -111,7 +116,7 @@ def run_layer_from_raster(Q_bits, K_bits, V_bits, grid, tile, t_text: int, block
     t_video = int(grid[0]) * int(grid[1]) * int(grid[2])
     Qr, Kr, Vr = (bits_to_device(x, device) for x in (Q_bits, K_bits, V_bits))
     shape = rb.make_shape(Qr, t_video, t_text, block)
-    Q, K, V, O, Or = (torch.empty_like(Qr) for _ in range(5))
+    Q, K, V, O, Or = (torch.full_like(Qr, float("nan")) for _ in range(5))
     for src, dst in ((Qr, Q), (Kr, K), (Vr, V)):
         rb.rsa_reorder_tokens(shape, grid, tile, 0, src, dst)
     buf = rb.allocate(Q, t_video, t_text, block)
@@ -133,7 +138,7 @@ def run_two_steps_reusing_masks(step1, step2, t_video: int, t_text: int, block: 
     Returns the step-1 mask / gate / R / A^pool and both outputs (bf16 bit patterns)."""
     Q1, K1, V1 = (bits_to_device(x, device) for x in step1)
     Q2, K2, V2 = (bits_to_device(x, device) for x in step2)
-    O1, O2 = torch.empty_like(Q1), torch.empty_like(Q2)
+    O1, O2 = torch.full_like(Q1, float("nan")), torch.full_like(Q2, float("nan"))
     buf = rb.allocate(Q1, t_video, t_text, block)
     flags = rb.RSA_RECTIFY_CRITICAL | rb.RSA_COMPENSATE
     rb.rectified_sparse_attention(Q1, K1, V1, O1, buf, sparsity, 0.0, 1, None, flags, None)

@@ -9,7 +9,9 @@ Tolerances:
   * pooled tensors / scores / A^pool / R: fp32-vs-fp64 rounding;
   * outputs: max-abs <= 2e-2 and relative L2 <= 5e-3 (bf16 inputs, fp32 accumulation; the
     probabilities are rounded to bf16 before P.V and the output to bf16, which alone gives
-    ~2.3e-3 relative L2 on the synthetic inputs).
+    ~2.3e-3 relative L2 on the synthetic inputs). The relative L2 is checked over all compared
+    rows together and for every query block on its own, so that one bad block cannot hide in
+    the norm of the others.
 Where a near-threshold block legitimately differs, the oracle output of that row is
 recomputed with the mask the GPU chose, so what is compared stays unique.
 """
@@ -124,5 +126,11 @@ def compare_head(gpu: dict, b: int, h: int, ref: dict, Qb, Kb, Vb, *, p: float =
     rel_l2 = float(np.linalg.norm(err) / max(np.linalg.norm(O_ref[rows]), 1e-300))
     assert max_abs <= OUT_MAX_ABS, f"max-abs {max_abs}"
     assert rel_l2 <= OUT_REL_L2, f"rel-L2 {rel_l2}"
-    stats.update(max_abs=max_abs, rel_l2=rel_l2, rows=int(rows.size), redo=len(redo))
+    worst_block = 0.0
+    for n in blocks:
+        r = part.tokens(n)
+        e = float(np.linalg.norm(O_gpu[r] - O_ref[r]) / max(np.linalg.norm(O_ref[r]), 1e-300))
+        assert e <= OUT_REL_L2, f"rel-L2 {e} of query block {n}"
+        worst_block = max(worst_block, e)
+    stats.update(max_abs=max_abs, rel_l2=rel_l2, rel_l2_worst_block=worst_block, rows=int(rows.size), redo=len(redo))
     return stats

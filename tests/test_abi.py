@@ -47,6 +47,7 @@ def test_block_counts_and_workspace(lib):
     (dict(head_dim=96), -3), (dict(block=32), -3), (dict(batch=0), -2), (dict(t_video=0), -2),
     (dict(t_text=-1), -2), (dict(stride_t=100), -2), (dict(stride_t=132), -2),
     (dict(t_video=128 * 5000), -3), (dict(scale=-1.0), -5),
+    (dict(stride_t=1 << 23), -3),            # 128 rows * 2^23 elements * 2 B = 2^31: past the 32-bit row offsets
 ])
 def test_bad_shapes_are_rejected(lib, kw, code):
     with pytest.raises(rb.RsaError) as e:
@@ -73,6 +74,13 @@ def test_null_and_range_arguments_are_rejected_before_launch(lib):
     attw = lambda flags, ws, nbytes: lib.rsa_sparse_attn_rectified(
         ctypes.byref(sh), one, one, one, one, one, one, one, one, one, one, flags, one, None, ws, nbytes, None)
     assert attw(3, None, 0) == -1 and attw(2, one, 16) == -4 and attw(2, ctypes.c_void_p(8), 1 << 30) == -4
+    # the entry point with built-in scratch: same checks, and shapes beyond its array are refused on the host
+    atts = lambda shape, flags, q=one: lib.rsa_sparse_attn_rectified_static(
+        ctypes.byref(shape), q, one, one, one, one, one, one, one, one, one, flags, one, None, None)
+    assert atts(sh, 8) == -5 and atts(sh, 3, None) == -1
+    t = 118800
+    big = _shape(heads=48, t_video=t, t_text=0, stride_b=48 * t * 128, stride_h=t * 128)
+    assert rb.rsa_workspace_bytes(big)[1] > rb.RSA_STATIC_SCRATCH_BYTES and atts(big, 3) == -4
     # adjacency mask: grid must multiply out to t_video, tile entries positive, radius in range
     i3 = lambda *v: (ctypes.c_int32 * 3)(*v)
     adj = lambda grid, tile, radius, out=one: lib.rsa_adjacency_mask(ctypes.byref(sh), grid, tile, radius, out, None)

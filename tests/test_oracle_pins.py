@@ -118,6 +118,36 @@ def test_oracle_equals_token_level_brute_force(seed, t_video, t_text, block, kep
         np.testing.assert_allclose(W.sum(axis=1), 1.0, rtol=1e-12)
 
 
+@pytest.mark.parametrize("rectify,compensate", [(False, False), (True, False), (False, True)])
+def test_rectification_switches_against_token_level_weights(rectify, compensate):
+    """Alg. 1 steps 20-22 taken apart: without step 20 the critical weights are the plain sparse softmax
+    (the brute-force critical weights divided by R_n), without steps 21-22 the compensated weights are
+    dropped. Built from the token-level weight matrix of the brute force, not from the oracle."""
+    rng = np.random.default_rng(23)
+    t_video, t_text, block, d, kept = 29, 5, 6, 4, 2
+    T = t_video + t_text
+    part = ro.partition(t_video, t_text, block)
+    base = _blockwise_constant(rng, part, d, amp=1.5)
+    Q = base + rng.normal(size=(T, d)) * 0.15
+    K = base + rng.normal(size=(T, d)) * 0.15
+    V = rng.normal(size=(T, d))
+    M = part.n_blocks
+    r = ro.rectified_layer_head(Q, K, V, t_video, t_text, block, (M - kept) / M, rectify=rectify, compensate=compensate)
+    b = brute_force_layer(Q, K, V, t_video, t_text, block, kept)
+    W, mask, R = np.asarray(b["W"]), np.asarray(b["mask"]), np.asarray(b["R"])
+    assert (np.asarray(b["Mc"]) & ~mask).any(), "nothing is compensated: the case proves nothing"
+    want = np.asarray(b["O"]).copy()
+    for n in range(part.n_video):
+        crit_tok = np.concatenate([np.arange(T)[part.tokens(m)] for m in range(M) if mask[n][m]])
+        is_crit = np.zeros(T, dtype=bool)
+        is_crit[crit_tok] = True
+        Wn = W[part.tokens(n)]
+        w_crit = np.where(is_crit, Wn, 0.0) / (1.0 if rectify else R[n])
+        w_comp = np.where(is_crit, 0.0, Wn) if compensate else 0.0
+        want[part.tokens(n)] = (w_crit + w_comp) @ V
+    np.testing.assert_allclose(r["O"], want, rtol=1e-11, atol=1e-12)
+
+
 # ------------------------------------------------------------------ the paper's worked numbers
 
 def test_intro_worked_example_single_token_blocks():
