@@ -46,9 +46,16 @@ typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));
 #ifndef RSA_NSTAGE
 #define RSA_NSTAGE 2
 #endif
-constexpr int NSTAGE = RSA_NSTAGE;  // LDS ring depth per group
+constexpr int KSTAGES = RSA_NSTAGE;  // LDS ring depth of the K tiles of a group
+constexpr int VSTAGES = 3;           // ... of its V^T tiles, which are read one phase later than the K tile of the same step
 #ifndef RSA_MWIN
-#define RSA_MWIN 8
+#define RSA_MWIN 4
+#endif
+#ifndef RSA_DSLOT
+#define RSA_DSLOT 2
+#endif
+#ifndef RSA_LSTRIDE
+#define RSA_LSTRIDE 1
 #endif
 constexpr int MWIN = RSA_MWIN;      // MFMA slots between the LDS read of a K operand and its use
 
@@ -72,9 +79,10 @@ struct AttnCfg {
   static constexpr int VPW = VINST / NW;
   static constexpr int KBUF = KVS * KCPR;   // 16-byte chunks per K buffer
   static constexpr int VBUF = D * VCPR;     // ... per V^T buffer
-  static constexpr int STAGE = KBUF + VBUF; // one ring stage
+  static constexpr int GROUP = KSTAGES * KBUF + VSTAGES * VBUF;   // 16-byte chunks of one group: [K stages | V^T stages]
   static_assert(KINST % NW == 0 && VINST % NW == 0, "loads must split evenly over the waves");
-  static_assert(NSTAGE == 2 && NGRP * NSTAGE * STAGE * 16 <= 160 * 1024, "the rings of all groups must fit the LDS of a CU");
+  static_assert(KSTAGES == 2 && NGRP * GROUP * 16 <= 160 * 1024, "the rings of all groups must fit the LDS of a CU");
+  static_assert(SPB == 1 || SPB == 2, "the main loop is unrolled twice: over the K stages and over the steps of a key block");
   static_assert(NGRP % 2 == 0 && BLK % KVS == 0, "groups pair up on the SIMDs; a block is a whole number of steps");
 };
 
@@ -121,7 +129,7 @@ __global__ __launch_bounds__(512, 1) void attn_kernel(Dims dm, AttnArgs a, int n
   using C = AttnCfg<D, BLK>;
   constexpr int KBUF = C::KBUF;
   constexpr int KVS = C::KVS, NGRP = C::NGRP;
-  __shared__ u32x4 lds_all[NGRP * NSTAGE * C::STAGE];   // per group a ring: stage st = [K rows | V^T rows]
+  __shared__ u32x4 lds_all[NGRP * C::GROUP];   // per group: KSTAGES K tiles [KVS][d], then VSTAGES V^T tiles [d][KVS]
 
   // ---- which (batch*head, query block) is this workgroup ---------------------------------
   const bool dense_all = (a.flags & RSA_DENSE) != 0;
@@ -129,7 +137,7 @@ __global__ __launch_bounds__(512, 1) void attn_kernel(Dims dm, AttnArgs a, int n
   const int wave_wg = __builtin_amdgcn_readfirstlane(tid / 64);
   const int grp = wave_wg / C::NW;                   // which of the query blocks of this workgroup
   const int wave = wave_wg % C::NW;                  // wave inside the group (groups g and g + NGRP/2 share their SIMDs)
-  u32x4* lds = lds_all + grp * (NSTAGE * C::STAGE);
+  u32x4* lds = lds_all + grp * C::GROUP;
   int bh;
   int qb_of[NGRP];                                   // query block of every group, -1: none
   {
@@ -203,28 +211,35 @@ __global__ __launch_bounds__(512, 1) void attn_kernel(Dims dm, AttnArgs a, int n
   constexpr int K_LDS_CLASS = C::NW * RK * C::KCPR * 16, V_LDS_CLASS = C::NW * RV * C::VCPR * 16;
   constexpr int K_LDS_PASS = K_ROWS_PER_PASS * C::KCPR * 16, V_LDS_PASS = V_ROWS_PER_PASS * C::VCPR * 16;
   const uint32_t ldsK_addr = (uint32_t)(uintptr_t)lds + wave * RK * (C::KCPR * 16);
-  const uint32_t ldsV_addr = (uint32_t)(uintptr_t)lds + KBUF * 16 + wave * RV * (C::VCPR * 16);
+  const uint32_t ldsV_addr = (uint32_t)(uintptr_t)lds + KSTAGES * KBUF * 16 + wave * RV * (C::VCPR * 16);
 
   const int nsteps = nlist * C::SPB;
   // The list is read through the constant address space: a scalar load, which neither waits
   // for nor is held up by the direct-to-LDS loads in flight (a vector load would be both).
+  // A dense row has no list (with RSA_DENSE every list pointer may be NULL): its loads read the first
+  // word of Q instead, and the index itself is taken.
   typedef const int32_t __attribute__((address_space(4))) * const_list_t;
-  const const_list_t clist = (const_list_t)(uintptr_t)list;
-  auto block_of = [&](int s) __attribute__((always_inline)) {
-    const int j = s / C::SPB;
-    return list ? clist[j] : j;
+  const const_list_t clist = (const_list_t)(uintptr_t)(list ? (const void*)list : (const void*)Qb);   // Q: never NULL, at least one row long
+  const bool has_list = list != nullptr;
+  // entry j of the list; past its end the last entry again (a valid block: the tile requested for a
+  // step that does not exist is never read)
+  auto list_entry = [&](int j) __attribute__((always_inline)) {
+    j = min(j, nlist - 1);
+    const int e = clist[has_list ? j : 0];
+    return has_list ? e : j;
   };
   // Requests for the K rows and the V^T rows of one step. Everything that does not depend on the
-  // step is worked out once, in bytes; a tile is prepared from its block index with scalar
-  // arithmetic only, and its LPS loads are then issued one at a time so that the caller can place
-  // them between its MFMAs.
+  // step is worked out once, in bytes: load ii of a wave is a per-lane byte offset (kvo / vvo, the
+  // pass folded in) from the tile's scalar base and a constant LDS offset from the stage's scalar
+  // base, so that a request is one scalar add into M0 and the load itself, and a tile is prepared
+  // from its block index with a dozen scalar instructions.
   const uint32_t kblock_bytes = (uint32_t)BLK * (uint32_t)dm.st * 2u;       // K rows of consecutive key blocks
   const uint32_t kstep_bytes = (uint32_t)KVS * (uint32_t)dm.st * 2u;        // ... of consecutive steps inside a block
   const uint32_t kpass_bytes = (uint32_t)K_ROWS_PER_PASS * (uint32_t)dm.st * 2u;
   const int64_t text_adjust = ((int64_t)dm.tv - (int64_t)dm.n * BLK) * dm.st * 2;   // text blocks start at T_v, not N*B
   const int last_video_count = dm.block_count(dm.n - 1), last_count = dm.block_count(dm.m - 1);
-  const char* Kbytes = reinterpret_cast<const char*>(Kb);
-  const char* Vtbytes = reinterpret_cast<const char*>(Vtb);
+  const uint64_t Kbytes = (uint64_t)(uintptr_t)Kb;
+  const uint64_t Vtbytes = (uint64_t)(uintptr_t)Vtb;
   constexpr uint32_t kVtBlockBytes = (uint32_t)D * BLK * 2u;
   auto count_of = [&](int m) __attribute__((always_inline)) {
     int c = BLK;
@@ -233,48 +248,62 @@ __global__ __launch_bounds__(512, 1) void attn_kernel(Dims dm, AttnArgs a, int n
     return c;
   };
   constexpr int LPS = C::KPW + C::VPW;           // loads per step per wave
+  uint32_t kvo[C::KPW], vvo[C::VPW];             // per-lane byte offsets of this wave's loads of a full tile
+#pragma unroll
+  for (int ii = 0; ii < C::KPW; ++ii) kvo[ii] = k_voff[ii % KOFF] + (uint32_t)(ii / KOFF) * kpass_bytes;
+#pragma unroll
+  for (int ii = 0; ii < C::VPW; ++ii) vvo[ii] = v_voff[ii % VOFF] + (uint32_t)((ii / VOFF) * (V_ROWS_PER_PASS * BLK * 2));
+  uint32_t kvw[C::KPW];                          // the K offsets in use: kvo, or clamped rows for a ragged block
+#pragma unroll
+  for (int ii = 0; ii < C::KPW; ++ii) kvw[ii] = kvo[ii];
+  int kvw_ragged = 0;
   struct Tile {
-    const char* kp;       // K rows of this step
-    const char* kblk;     // K rows of the whole block (ragged path)
-    const char* vp;       // V^T rows of this step
-    uint32_t kdst, vdst;  // LDS byte addresses of the stage
-    int kv_count, part;
+    uint64_t kp;          // K rows of this step (of the whole block when it is ragged)
+    uint64_t vp;          // V^T rows of this step
+    uint32_t kdst, vdst;  // LDS byte addresses of this wave's first load into the stage
   };
-  auto prepare_tile = [&](int m, int s, int st) __attribute__((always_inline)) {
-    Tile t;
-    t.part = s % C::SPB;
-    t.kv_count = count_of(m);
-    t.kblk = Kbytes + ((uint64_t)(uint32_t)m * kblock_bytes + (uint64_t)(m >= dm.n ? text_adjust : 0));
-    t.kp = t.kblk + (uint32_t)t.part * kstep_bytes;
-    t.vp = Vtbytes + ((uint64_t)(uint32_t)m * kVtBlockBytes + (uint32_t)t.part * (KVS * 2u));
-    t.kdst = ldsK_addr + st * (C::STAGE * 16);
-    t.vdst = ldsV_addr + st * (C::STAGE * 16);
-    return t;
+  // The key block whose tiles are being requested: start of its K rows and V^T rows, valid keys.
+  uint64_t blk_kp = 0, blk_vp = 0;
+  int blk_count = BLK;
+  // A tile is prepared in short pieces of scalar work so that the caller can put one behind each
+  // of its first MFMAs: open_block for the first step of a key block, step_of_block for every step.
+  // A ragged key block (the last video block, the last text block) adds vector work: K rows past
+  // the block end re-read its last row (masked later; V^T is zero-padded in HBM), with per-lane
+  // offsets from the start of the block.
+  auto open_block = [&](int m) __attribute__((always_inline)) {
+    blk_kp = Kbytes + ((uint64_t)(uint32_t)m * kblock_bytes + (uint64_t)(m >= dm.n ? text_adjust : 0));
+    blk_vp = Vtbytes + (uint64_t)(uint32_t)m * kVtBlockBytes;
+    blk_count = count_of(m);
   };
-  // Load `idx` of a tile whose key block is full.
+  auto step_of_block = [&](Tile& t, uint32_t part, int kst, int vst) __attribute__((always_inline)) {
+    t.kp = blk_kp + part * kstep_bytes;
+    t.vp = blk_vp + part * (KVS * 2u);
+    t.kdst = ldsK_addr + kst * (KBUF * 16);
+    t.vdst = ldsV_addr + vst * (C::VBUF * 16);
+    if (kvw_ragged) {
+#pragma unroll
+      for (int ii = 0; ii < C::KPW; ++ii) kvw[ii] = kvo[ii];
+      kvw_ragged = 0;
+    }
+    if (blk_count < BLK) {
+      t.kp = blk_kp;
+#pragma unroll
+      for (int ii = 0; ii < C::KPW; ++ii) {
+        int r = (int)part * KVS + (ii / KOFF) * K_ROWS_PER_PASS + k_r0[ii % KOFF];
+        r = r < blk_count ? r : blk_count - 1;
+        kvw[ii] = (uint32_t)((r * dm.st + k_col[ii % KOFF]) * 2);
+      }
+      kvw_ragged = 1;
+    }
+  };
   auto issue_load = [&](const Tile& t, int idx) __attribute__((always_inline)) {
     if (idx < C::KPW) {
       const int ii = idx;
-      dma16_sv(t.kdst + (ii / KOFF) * K_LDS_PASS + (ii % KOFF) * K_LDS_CLASS,
-               t.kp + (ii / KOFF) * kpass_bytes, k_voff[ii % KOFF], lds);
+      dma16_sv_at(t.kdst, (ii / KOFF) * K_LDS_PASS + (ii % KOFF) * K_LDS_CLASS, t.kp, kvw[ii], lds);
     } else {
       const int ii = idx - C::KPW;
-      dma16_sv(t.vdst + (ii / VOFF) * V_LDS_PASS + (ii % VOFF) * V_LDS_CLASS,
-               t.vp + (ii / VOFF) * (V_ROWS_PER_PASS * BLK * 2), v_voff[ii % VOFF], lds);
+      dma16_sv_at(t.vdst, (ii / VOFF) * V_LDS_PASS + (ii % VOFF) * V_LDS_CLASS, t.vp, vvo[ii], lds);
     }
-  };
-  // All loads of a tile whose key block is ragged (the last video block, the last text block):
-  // K rows past the block end re-read its last row (masked later); V^T is zero-padded in HBM.
-  auto issue_ragged = [&](const Tile& t) __attribute__((always_inline)) {
-#pragma unroll
-    for (int ii = 0; ii < C::KPW; ++ii) {
-      int r = t.part * KVS + (ii / KOFF) * K_ROWS_PER_PASS + k_r0[ii % KOFF];
-      r = r < t.kv_count ? r : t.kv_count - 1;
-      dma16_sv(t.kdst + (ii / KOFF) * K_LDS_PASS + (ii % KOFF) * K_LDS_CLASS, t.kblk,
-               (uint32_t)((r * dm.st + k_col[ii % KOFF]) * 2), lds);
-    }
-#pragma unroll
-    for (int ii = C::KPW; ii < LPS; ++ii) issue_load(t, ii);
   };
 
   // ---- loop-invariant LDS read positions (16-byte chunk index inside stage 0, tile 0) ----
@@ -283,7 +312,7 @@ __global__ __launch_bounds__(512, 1) void attn_kernel(Dims dm, AttnArgs a, int n
 #pragma unroll
   for (int ks = 0; ks < C::KS; ++ks) kread[ks] = lds + swizzled<C::KCPR>(l32, 2 * ks + hf);
 #pragma unroll
-  for (int pc = 0; pc < C::PC; ++pc) vread[pc] = lds + KBUF + swizzled<C::VCPR>(l32, 2 * pc + hf);
+  for (int pc = 0; pc < C::PC; ++pc) vread[pc] = lds + KSTAGES * KBUF + swizzled<C::VCPR>(l32, 2 * pc + hf);
 
   // ---- Q as the B operand of S^T = K Q^T, resident in registers --------------------------
   const int q_count = dm.block_count(qb);
@@ -314,13 +343,16 @@ __global__ __launch_bounds__(512, 1) void attn_kernel(Dims dm, AttnArgs a, int n
   // Two groups of waves share every SIMD (wave w of group 0 and wave w of group 1). They run
   // the same sequence  [M(s) | barrier | V(s) | barrier] ...  one barrier apart, so that while
   // one group issues MFMAs the other does its softmax on the VALU:
-  //   M(s): O^T += V^T P^T of step s-1 (operands already in registers), then S^T = K Q^T of step s
-  //         from ring stage s % 2; the loads of tile s+1 go out one per MFMA slot
-  //   V(s): fetch the V^T operands of step s into registers (their LDS latency hides behind the
-  //         softmax), mask, online softmax -> P as bf16 B operands; fetch the list entry of step
-  //         s+2; wait for tile s+1
-  // The barrier after V(s) publishes tile s+1 to the group and, because every LDS read of
-  // stage (s-1) % 2 has returned by then, frees that stage for the requests in M(s+1).
+  //   M(s): O^T += V^T P^T of step s-1, then S^T = K Q^T of step s: matrix instructions only, the A
+  //         operand of each read from LDS a fixed number of slots ahead (V^T tile of step s-1 from
+  //         its ring stage (s-1) % 3, K tile of step s from stage s % 2); the loads of tile s+1
+  //         (K into stage (s+1) % 2, V^T into stage (s+1) % 3) go out one per MFMA slot
+  //   V(s): mask, online softmax -> P as bf16 B operands (VALU only); fetch the list entry of step
+  //         s+2; wait for tile s+1; read the first V^T operands of M(s+1) ahead of the barrier
+  // The barrier after V(s) publishes tile s+1 to the group. A K stage is rewritten two steps
+  // after it was read, a V^T stage (read in M(s+1), one phase after its K tile) three steps after
+  // it was filled: by then every wave of the group has passed the barrier that follows its last
+  // read.
   int m_nxt = 0;          // key block of the step after the current one
   int kvc_cur = BLK;      // valid keys in the block of the current step
   int kvc_nxt = BLK;
@@ -331,86 +363,118 @@ __global__ __launch_bounds__(512, 1) void attn_kernel(Dims dm, AttnArgs a, int n
   };
   floatx16 sacc[C::KT];
   u32x4 pb[C::PC];            // probabilities as bf16 B operands, 16 keys per entry
-  bf16x8 vop[C::PC][C::DT];   // V^T operands of the step whose P V product is still to come
 #pragma unroll
-  for (int pc = 0; pc < C::PC; ++pc) {
-    pb[pc] = u32x4{0u, 0u, 0u, 0u};
-#pragma unroll
-    for (int dt = 0; dt < C::DT; ++dt) vop[pc][dt] = __builtin_bit_cast(bf16x8, u32x4{0u, 0u, 0u, 0u});
-  }
+  for (int pc = 0; pc < C::PC; ++pc) pb[pc] = u32x4{0u, 0u, 0u, 0u};
 
-  // M(s) as one fixed sequence of NPV + NQK MFMA slots: the P V product of step s-1 (operands in
-  // registers), then K Q^T of step s. The K operand of
-  // slot i is read from LDS W slots ahead of its MFMA into a ring of W registers, so LDS latency
-  // stays behind MFMAs that already have their operands; the order is pinned slot by slot.
-  auto m_phase = [&](auto stc, auto pvc, auto qkc, int s) __attribute__((always_inline)) {
-    constexpr int ST = decltype(stc)::value;
-    constexpr bool do_pv = decltype(pvc)::value != 0, do_qk = decltype(qkc)::value != 0;
-    constexpr int NPV = C::PC * C::DT, NQK = C::KS * C::KT, NSLOT = NPV + NQK;
-    constexpr int W = MWIN;
-    constexpr int DSLOT = 1;                          // the slot in which the requests for the next tile start
-    const bool more = s + 1 < nsteps;
-    Tile nt = {};
-    bool full = true;
-    bf16x8 kring[W];
-    auto read_k = [&](int slot) __attribute__((always_inline)) {           // slot >= NPV
-      const int q = slot - NPV, k2 = q / C::KT, t = q % C::KT;
-      kring[slot % W] = __builtin_bit_cast(bf16x8, kread[k2][ST * C::STAGE + t * 32 * C::KCPR]);
-    };
-    if (do_qk) {
+  // M(s) is one fixed sequence of NPV + NQK MFMA slots: the P V product of step s-1, then K Q^T
+  // of step s. The A operand of a slot (16 bytes per lane of the V^T or K tile) is read from LDS W
+  // slots ahead of its MFMA into a ring of W registers, so that LDS latency stays behind MFMAs
+  // that already have their operands; the first W operands of a phase are read at the end of the
+  // softmax phase before it. The order is pinned slot by slot.
+  constexpr int NPV = C::PC * C::DT, NQK = C::KS * C::KT, NSLOT = NPV + NQK;
+  constexpr int W = MWIN;
+  static_assert(W - W / 2 <= 4, "the operand waits are written out for at most four reads left outstanding");
+  static_assert(NPV >= W && NQK >= W, "the operands read ahead of a phase all belong to its first product");
+  bf16x8 ring[W];
 #pragma unroll
-      for (int j = NPV; j < W && j < NSLOT; ++j) read_k(j);
+  for (int i = 0; i < W; ++i) ring[i] = __builtin_bit_cast(bf16x8, u32x4{0u, 0u, 0u, 0u});
+  int vst = 0;                // V^T ring stage of the current step (s % VSTAGES)
+  const u32x4* vcur[C::PC];   // vread[] moved to the V^T stage whose P V product comes next
+#pragma unroll
+  for (int pc = 0; pc < C::PC; ++pc) vcur[pc] = vread[pc];
+  auto read_v_operand = [&](int slot) __attribute__((always_inline)) {      // slot < NPV
+    const int pc = slot / C::DT, dt = slot % C::DT;
+    ring[slot % W] = __builtin_bit_cast(bf16x8, vcur[pc][dt * 32 * C::VCPR]);
+  };
+
+  auto m_phase = [&](auto stc, auto pvc, auto qkc, int s) __attribute__((always_inline)) {
+    constexpr int ST = decltype(stc)::value;          // s modulo the unroll factor: gives the K stage and the part of the key block
+    constexpr bool do_pv = decltype(pvc)::value != 0, do_qk = decltype(qkc)::value != 0;
+    constexpr int DSLOT = RSA_DSLOT;                  // the slot in which the requests for the next tile start
+    constexpr int LSTRIDE = RSA_LSTRIDE;              // ... and the slots from one request to the next
+    constexpr int FIRST = do_pv ? 0 : NPV, LAST = do_qk ? NSLOT : NPV;     // slots that hold an MFMA
+    constexpr int WB = W / 2;                         // operands are waited for WB at a time
+    Tile nt = {};
+    auto read_k_operand = [&](int slot) __attribute__((always_inline)) {   // slot >= NPV
+      const int q = slot - NPV, k2 = q / C::KT, t = q % C::KT;
+      ring[slot % W] = __builtin_bit_cast(bf16x8, kread[k2][(ST % KSTAGES) * KBUF + t * 32 * C::KCPR]);
+    };
+    auto read_operand = [&](int slot) __attribute__((always_inline)) {
+      if (slot < NPV) read_v_operand(slot); else read_k_operand(slot);
+    };
+    // The wave that feeds the matrix pipe goes first wherever the two waves of a SIMD compete for an
+    // issue slot: without this the older wave of the two wins, and the MFMA phases of the younger
+    // group run a fifth longer than those of the other.
+    __builtin_amdgcn_s_setprio(3);
+    if (!do_pv) {
+      // first step of a list: nothing was read ahead
+#pragma unroll
+      for (int j = FIRST; j < FIRST + W && j < LAST; ++j) read_operand(j);
     }
     __builtin_amdgcn_sched_barrier(0);
 #pragma unroll
-    for (int i = 0; i < NSLOT; ++i) {
-      // one load of the tile of step s+1 per slot, behind the MFMA of the slot before
-      if (i == DSLOT && more && !full) issue_ragged(nt);
-      if (i >= DSLOT && i - DSLOT < LPS) {
-        if (more && full) issue_load(nt, i - DSLOT);
+    for (int i = FIRST; i < LAST; ++i) {
+      const int e = i - FIRST;                        // position among the MFMAs of this phase
+      // The operands of slots i .. i+WB-1 have arrived once at most the reads behind them are
+      // outstanding: one wait per WB slots, and none is needed in between.
+      if (e % WB == 0) {
+        const int behind = min(W - WB, max(LAST - i - WB, 0));
+        // vmcnt and expcnt fields at "no wait", lgkmcnt = behind
+        if (behind == 0) __builtin_amdgcn_s_waitcnt(0xC07F);
+        else if (behind == 1) __builtin_amdgcn_s_waitcnt(0xC17F);
+        else if (behind == 2) __builtin_amdgcn_s_waitcnt(0xC27F);
+        else if (behind == 3) __builtin_amdgcn_s_waitcnt(0xC37F);
+        else __builtin_amdgcn_s_waitcnt(0xC47F);
+        __builtin_amdgcn_sched_barrier(0);
       }
+      // one load of the tile of step s+1 per slot, behind the MFMA of the slot before
+      if (do_qk && e >= DSLOT && (e - DSLOT) % LSTRIDE == 0 && (e - DSLOT) / LSTRIDE < LPS) issue_load(nt, (e - DSLOT) / LSTRIDE);
       if (i < NPV) {
         const int pc = i / C::DT, dt = i % C::DT;
-        if (do_pv)
-          oacc[dt] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(vop[pc][dt], __builtin_bit_cast(bf16x8, pb[pc]), oacc[dt], 0, 0, 0);
+        oacc[dt] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(ring[i % W], __builtin_bit_cast(bf16x8, pb[pc]), oacc[dt], 0, 0, 0);
       } else {
         const int q = i - NPV, k2 = q / C::KT, t = q % C::KT;
-        if (do_qk) {
-          floatx16 c0 = sacc[t];
-          if (k2 == 0) {
+        floatx16 c0 = sacc[t];
+        if (k2 == 0) {
 #pragma unroll
-            for (int r = 0; r < 16; ++r) c0[r] = 0.f;           // folds into the instruction's constant C operand
-          }
-          sacc[t] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(kring[i % W], qreg[k2], c0, 0, 0, 0);
+          for (int r = 0; r < 16; ++r) c0[r] = 0.f;           // folds into the instruction's constant C operand
+        }
+        sacc[t] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(ring[i % W], qreg[k2], c0, 0, 0, 0);
+      }
+      // the ring entry this slot used takes the operand of slot i + W
+      if (i + W < LAST) read_operand(i + W);
+      if (do_qk && e < 2) {
+        // behind the first MFMAs, so that the matrix pipe starts as soon as the barrier opens:
+        // addresses of the tile of step s+1. The loop is unrolled over the steps of a key block, so
+        // whether that step opens a new block (its list entry came in during V(s-1)) is known at
+        // compile time. A list that ends with this step requests the tile of its last entry once
+        // more, into a stage nobody reads again.
+        __builtin_amdgcn_sched_barrier(0);
+        constexpr int PART_NEXT = (ST + 1) % C::SPB;
+        if (e == 0) {
+          if (PART_NEXT == 0) open_block(m_nxt);
+          kvc_nxt = blk_count;
+        } else {
+          step_of_block(nt, PART_NEXT, (ST + 1) % KSTAGES, vst + 1 >= VSTAGES ? 0 : vst + 1);
         }
       }
-      // the ring entry this slot used (or will never use) takes the operand of slot i + W
-      if (do_qk && i + W >= NPV && i + W < NSLOT) read_k(i + W);
-      if (i == 0) {
-        // behind the first MFMA, so that the matrix pipe starts as soon as the barrier opens:
-        // addresses of the tile of step s+1 (its list entry came in during V(s-1))
-        __builtin_amdgcn_sched_barrier(0);
-        if (more) nt = prepare_tile(m_nxt, s + 1, 1 - ST);
-        kvc_nxt = nt.kv_count;
-        full = nt.kv_count == BLK;
-      }
       __builtin_amdgcn_sched_barrier(0);
+    }
+    // a phase with fewer slots than loads (the first step of a list has no P V product) sends the rest here
+#pragma unroll
+    for (int idx = 0; idx < LPS; ++idx) {
+      if (do_qk && DSLOT + idx * LSTRIDE >= LAST - FIRST) issue_load(nt, idx);
     }
   };
 
   auto v_phase = [&](auto stc, int s) __attribute__((always_inline)) {
     constexpr int ST = decltype(stc)::value;
+    __builtin_amdgcn_s_setprio(0);
     {
-#pragma unroll
-      for (int pc = 0; pc < C::PC; ++pc)
-#pragma unroll
-        for (int dt = 0; dt < C::DT; ++dt)
-          vop[pc][dt] = __builtin_bit_cast(bf16x8, vread[pc][ST * C::STAGE + dt * 32 * C::VCPR]);
-      __builtin_amdgcn_sched_barrier(0);
       const int kv_count = kvc_cur;
       // accumulator register r of key tile t is key part*KVS + 32t + 8(r/4) + 4*hf + r%4 of the block
       if (kv_count < BLK) {
-        const int part = s % C::SPB;
+        constexpr int part = ST % C::SPB;
 #pragma unroll
         for (int t = 0; t < C::KT; ++t)
 #pragma unroll
@@ -458,30 +522,32 @@ __global__ __launch_bounds__(512, 1) void attn_kernel(Dims dm, AttnArgs a, int n
       }
       lpart += rs;
     }
-    // the list entry of step s+2 for M(s+1), fetched here so that its wait is the one below
-    m_nxt = s + 2 < nsteps ? block_of(s + 2) : 0;
+    // the list entry of step s+2 (where that step opens a key block) for M(s+1), fetched a phase ahead
+    if ((ST + 2) % C::SPB == 0) m_nxt = list_entry((s + 2) / C::SPB);
     kvc_cur = kvc_nxt;
     // the probabilities are complete here: nothing of the softmax may sink behind the barrier
     // into the MFMA phase, where it would take the other group's VALU time
 #pragma unroll
     for (int pc = 0; pc < C::PC; ++pc) asm volatile("" : "+v"(pb[pc]));
     asm volatile("" : "+v"(lpart), "+v"(mref));
-    // tile s+1 has landed (this wave's share; the barrier that follows covers the group), and
-    // every LDS read issued so far has returned, so stage ST may be overwritten after it
-    __builtin_amdgcn_s_waitcnt(0x0070);          // vmcnt(0), lgkmcnt(0)
+    // the first V^T operands of M(s+1), from the stage of this step (published a whole step ago)
+#pragma unroll
+    for (int pc = 0; pc < C::PC; ++pc) vcur[pc] = vread[pc] + vst * C::VBUF;
+#pragma unroll
+    for (int j = 0; j < W; ++j) read_v_operand(j);
+    vst = vst + 1 >= VSTAGES ? 0 : vst + 1;
+    // tile s+1 has landed (this wave's share; the barrier that follows covers the group)
+    __builtin_amdgcn_s_waitcnt(0x0F70);          // vmcnt(0)
   };
 
   if (nsteps > 0) {
-    const int m0 = block_of(0);
-    const Tile t0 = prepare_tile(m0, 0, 0);
-    if (t0.kv_count == BLK) {
+    Tile t0;
+    open_block(list_entry(0));
+    step_of_block(t0, 0, 0, 0);
 #pragma unroll
-      for (int i = 0; i < LPS; ++i) issue_load(t0, i);
-    } else {
-      issue_ragged(t0);
-    }
-    kvc_cur = t0.kv_count;
-    m_nxt = nsteps > 1 ? block_of(1) : 0;
+    for (int i = 0; i < LPS; ++i) issue_load(t0, i);
+    kvc_cur = blk_count;
+    if (C::SPB == 1) m_nxt = list_entry(1);       // otherwise V(0) fetches it
   }
   __builtin_amdgcn_s_waitcnt(0x0070);
   group_barrier();                  // tile 0 of both groups is in LDS

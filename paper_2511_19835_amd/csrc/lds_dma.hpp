@@ -21,6 +21,12 @@ __device__ __forceinline__ void dma16_sv(uint32_t lds_addr, const void* sbase, u
   asm volatile("s_mov_b32 m0, %0\n\tglobal_load_lds_dwordx4 %1, %2"
                ::"s"(__builtin_amdgcn_readfirstlane(lds_addr)), "v"(voff), "s"(ps), "r"(fence) : "memory");
 }
+// The same with the LDS address given as a wave-uniform base plus a wave-uniform offset, added straight
+// into M0: one scalar instruction and the load, whatever the offset.
+__device__ __forceinline__ void dma16_sv_at(uint32_t lds_base, uint32_t lds_off, uint64_t sbase, uint32_t voff, void* fence) {
+  asm volatile("s_add_u32 m0, %0, %1\n\tglobal_load_lds_dwordx4 %2, %3"
+               ::"s"(lds_base), "s"(lds_off), "v"(voff), "s"(sbase), "r"(fence) : "memory", "scc");
+}
 __device__ __forceinline__ void dma16_v(uint32_t lds_addr, const void* gptr, void* fence) {
   asm volatile("s_mov_b32 m0, %0\n\tglobal_load_lds_dwordx4 %1, off"
                ::"s"(__builtin_amdgcn_readfirstlane(lds_addr)), "v"(gptr), "r"(fence) : "memory");
