@@ -1,14 +1,16 @@
 // Block-sparse flash attention with the rectification fused into the epilogue
 // (paper Sec. 3.1 sparse attention, Alg. 1 steps 16-17; Sec. 4.1 / 4.2, Alg. 1 steps 19-23).
 //
-// A workgroup is eight waves and owns 256 query rows of one (batch, head): groups of BLK/32 waves,
-// one group per query block (two at BLK = 128, four at BLK = 64), one wave per 32 query rows,
-// groups g and g + NGRP/2 on the same SIMDs. Video query blocks walk their
-// compact, ascending list of critical key blocks; text query blocks (and every block under
-// RSA_DENSE) walk all M key blocks. Key blocks are consumed in steps of KVS keys. For each
-// step the K rows [KVS][d] and the channel-major V rows [d][KVS] of a group are brought into
-// its own two-stage LDS ring by direct-to-LDS loads (global_load_lds_dwordx4: no staging
-// registers), one step ahead. Each wave computes, with v_mfma_f32_32x32x16_bf16,
+// The kernel is persistent: one workgroup of eight waves per CU, in groups of BLK/32 waves (two groups
+// at BLK = 128, four at BLK = 64; one wave per 32 query rows; groups g and g + NGRP/2 on the same
+// SIMDs). A group works through a sequence of items -- query blocks of some (batch, head) -- that
+// schedule_kernel dealt to it, as one unbroken stream of steps: a video query block walks its
+// compact, ascending list of critical key blocks, a text query block (and every block under
+// RSA_DENSE) all M key blocks, KVS keys per step. For each step the K rows [KVS][d] and the
+// channel-major V rows [d][KVS] are brought into the group's own LDS rings by direct-to-LDS loads
+// (global_load_lds_dwordx4: no staging registers), one step ahead -- also across the boundary
+// between two items, so the matrix pipe never drains. Each wave computes, with
+// v_mfma_f32_32x32x16_bf16,
 //     S^T = K Q^T      (M = key, N = query, k = channel)      -> accumulators: one query
 //     O^T += V^T P^T   (M = channel, N = query, k = key)         column per lane
 // so the online softmax is lane-local except for one exchange between the two half-waves,
@@ -16,22 +18,18 @@
 // needs for the second (rsa_pool stores V in that key order).
 //
 // A step of a group is two phases, separated by workgroup barriers: an MFMA phase (the P V
-// product of the previous step, then K Q^T of this one: nothing but matrix instructions, LDS
-// operand reads a fixed number of slots ahead and the requests for the next tile, one per
-// slot) and a softmax phase (VALU only; it also moves the step's V^T operands to registers).
-// The two groups run one barrier apart, so that on every SIMD one wave feeds the matrix pipe
-// while the other uses the VALU. Measured against one workgroup per query block with the
-// softmax interleaved into each wave's own MFMA stream (two workgroups per CU): 14 % fewer
-// core cycles, 8 % less time (the clock drops further under the power cap).
-// Epilogue: O = R_n * acc / l + C_n, C_n = sum_{m: not kept and M_c} A^pool[n][m] v^pool_m
-// (computed beforehand by compensation_kernel into the workspace).
+// product of the previous step, then K Q^T of this one: matrix instructions, their LDS operand
+// reads a few slots ahead and the requests for the next tile, one per slot) and a softmax phase
+// (VALU only). The groups run one barrier apart, so that on every SIMD one wave feeds the matrix
+// pipe while the other uses the VALU. When an item ends its output is written in the softmax phase
+// of the next item's first step: O = R_n * acc / l + C_n, C_n = sum_{m: not kept and M_c}
+// A^pool[n][m] v^pool_m (computed beforehand by compensation_kernel into the workspace).
 //
 // 4*B*B*d flop per (query block, key block) pair against 2*B*d*2 bytes of K/V traffic.
-// Workgroups are ordered so that the long dense text rows start first and each XCD
-// (workgroup id modulo 8) owns a contiguous range of launch positions of a head;
-// row_order_kernel maps positions to video query blocks so that blocks with similar lists
-// are resident together (the two of a workgroup are neighbours in that order) and share
-// K/V tiles in the XCD's L2.
+// row_order_kernel sorts the video query blocks of a head by their first kept key blocks;
+// schedule_kernel deals that order (long dense rows first) to the groups so that each XCD
+// (workgroup id modulo 8) owns a contiguous range of it, groups resident together walk similar
+// lists and share K/V tiles in the XCD's L2, and all groups end within one item of each other.
 #include "rsa_common.hpp"
 #include "lds_dma.hpp"
 
@@ -40,9 +38,6 @@ namespace {
 
 constexpr float kLog2e = 1.4426950408889634f;
 typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));
-#ifndef RSA_KVS
-#define RSA_KVS 64
-#endif
 #ifndef RSA_NSTAGE
 #define RSA_NSTAGE 2
 #endif
@@ -54,9 +49,6 @@ constexpr int VSTAGES = 3;           // ... of its V^T tiles, which are read one
 #ifndef RSA_DSLOT
 #define RSA_DSLOT 2
 #endif
-#ifndef RSA_LSTRIDE
-#define RSA_LSTRIDE 1
-#endif
 constexpr int MWIN = RSA_MWIN;      // MFMA slots between the LDS read of a K operand and its use
 
 template <int D, int BLK>
@@ -64,8 +56,9 @@ struct AttnCfg {
   static constexpr int NW = BLK / 32;       // waves per group (one per 32 query rows)
   static constexpr int NGRP = 8 / NW;       // groups = query blocks per workgroup: eight waves, two per SIMD
   static constexpr int NTHR = 64 * NW * NGRP;
-  // keys per step; halved where four rings of 64 keys x 128 channels would not fit the LDS
-  static constexpr int KVS = (BLK == 64 && D == 128) ? RSA_KVS / 2 : RSA_KVS;
+  // keys per step: half a key block, so that every key block is two steps and every item an even
+  // number of them (the loop over the steps is unrolled twice)
+  static constexpr int KVS = BLK / 2;
   static constexpr int SPB = BLK / KVS;     // steps per key block
   static constexpr int KT = KVS / 32;       // key tiles of S^T per step
   static constexpr int KS = D / 16;         // k-steps of K Q^T
@@ -82,7 +75,7 @@ struct AttnCfg {
   static constexpr int GROUP = KSTAGES * KBUF + VSTAGES * VBUF;   // 16-byte chunks of one group: [K stages | V^T stages]
   static_assert(KINST % NW == 0 && VINST % NW == 0, "loads must split evenly over the waves");
   static_assert(KSTAGES == 2 && NGRP * GROUP * 16 <= 160 * 1024, "the rings of all groups must fit the LDS of a CU");
-  static_assert(SPB == 1 || SPB == 2, "the main loop is unrolled twice: over the K stages and over the steps of a key block");
+  static_assert(SPB == 2, "the main loop is unrolled twice: over the K stages and over the steps of a key block");
   static_assert(NGRP % 2 == 0 && BLK % KVS == 0, "groups pair up on the SIMDs; a block is a whole number of steps");
 };
 
@@ -122,68 +115,132 @@ constexpr float kLazyBits = 6.0f;
 
 template <int V>
 struct IntC { static constexpr int value = V; };
+// f(IntC<I>{}) for I = FROM .. TO-1, unrolled at compile time (the index is a constant inside f)
+template <int FROM, int TO, class F>
+__device__ __forceinline__ void static_for(F&& f) {
+  if constexpr (FROM < TO) {
+    f(IntC<FROM>{});
+    static_for<FROM + 1, TO>(f);
+  }
+}
+
+// Work of the persistent attention kernel. An item is one query block of one (batch, head); a slot
+// is one group of waves of one resident workgroup and works through a sequence of items.
+//   table != NULL: schedule_kernel dealt the items to the slots (balanced by their number of steps,
+//                  neighbouring rows of the launch order to neighbouring slots at the same time);
+//   table == NULL: item i goes to slot i % n_slots (no workspace: index order).
+struct SchedArgs {
+  const int32_t* table;     // [slots][cap] item records: (batch*heads index) * RSA_MAX_BLOCKS + query block
+  const int32_t* nitems;    // [slots]
+  const int32_t* total;     // [slots] steps of all items of the slot
+  int cap;
+  int n_items, n_dense;     // all items; the dense ones (text query blocks, or every block under RSA_DENSE) come first
+  int dense_per_bh, dense_first;
+};
+
+// Entries of a video query block's list as every kernel here takes them: the count that
+// rsa_select_blocks wrote, held to 1 .. M so that no count, whatever it is, can derail the loops.
+__device__ __forceinline__ int list_length(const AttnArgs& a, const Dims& dm, size_t vrow) {
+  typedef const int32_t __attribute__((address_space(4))) * const_i32_t;     // scalar loads
+  const int c = ((const_i32_t)(uintptr_t)a.count)[vrow];
+  return min(max(c, 1), dm.m);
+}
 
 template <int D, int BLK>
-__global__ __launch_bounds__(512, 1) void attn_kernel(Dims dm, AttnArgs a, int n_text_items,
-                                                                                  int chunk) {
+__global__ __launch_bounds__(512, 1) void attn_kernel(Dims dm, AttnArgs a, SchedArgs sc) {
   using C = AttnCfg<D, BLK>;
   constexpr int KBUF = C::KBUF;
   constexpr int KVS = C::KVS, NGRP = C::NGRP;
   __shared__ u32x4 lds_all[NGRP * C::GROUP];   // per group: KSTAGES K tiles [KVS][d], then VSTAGES V^T tiles [d][KVS]
 
-  // ---- which (batch*head, query block) is this workgroup ---------------------------------
   const bool dense_all = (a.flags & RSA_DENSE) != 0;
   const int tid = threadIdx.x;
   const int wave_wg = __builtin_amdgcn_readfirstlane(tid / 64);
-  const int grp = wave_wg / C::NW;                   // which of the query blocks of this workgroup
+  const int grp = wave_wg / C::NW;                   // which group of this workgroup
   const int wave = wave_wg % C::NW;                  // wave inside the group (groups g and g + NGRP/2 share their SIMDs)
-  u32x4* lds = lds_all + grp * C::GROUP;
-  int bh;
-  int qb_of[NGRP];                                   // query block of every group, -1: none
-  {
-    const int id = blockIdx.x;
-    if (id < n_text_items) {           // long dense rows first, two per workgroup
-      const int per = dense_all ? dm.m : dm.mt, pairs = (per + NGRP - 1) / NGRP;
-      bh = id / pairs;
-      const int r0 = NGRP * (id % pairs), first = dense_all ? 0 : dm.n;
-#pragma unroll
-      for (int g = 0; g < NGRP; ++g) qb_of[g] = r0 + g < per ? first + r0 + g : -1;
-    } else {
-      const int v = id - n_text_items;
-      const int xcd = v & 7, j = v >> 3, pairs = (chunk + NGRP - 1) / NGRP;
-      bh = j / pairs;
-      const int p0 = xcd * chunk + NGRP * (j % pairs);              // launch positions p0 .. p0 + NGRP - 1
-      const int pend = min(dm.n, (xcd + 1) * chunk);
-      if (p0 >= pend) return;          // whole workgroup leaves before any barrier
-#pragma unroll
-      for (int g = 0; g < NGRP; ++g) {
-        qb_of[g] = -1;
-        if (p0 + g < pend) qb_of[g] = a.row_order ? a.row_order[(size_t)bh * dm.n + p0 + g] : p0 + g;
-      }
-    }
-  }
-  auto steps_of = [&](int qbx) __attribute__((always_inline)) {
-    if (qbx < 0) return 0;
-    const bool sp = !dense_all && qbx < dm.n;
-    return (sp ? a.count[(size_t)bh * dm.n + qbx] : dm.m) * C::SPB;
-  };
-  int smax = 0;                                      // every group turns the loop this often
-#pragma unroll
-  for (int g = 0; g < NGRP; ++g) smax = max(smax, steps_of(qb_of[g]));
-  const int qb = qb_of[grp] < 0 ? 0 : qb_of[grp];
-  const bool active = qb_of[grp] >= 0;
-  const int b = bh / dm.heads, h = bh % dm.heads;
-  const bool sparse_row = !dense_all && qb < dm.n;
-  const size_t vrow = (size_t)bh * dm.n + qb;      // row of the per-video-block tensors
-  const int nlist = !active ? 0 : sparse_row ? a.count[vrow] : dm.m;
-  const int32_t* list = sparse_row ? a.block_idx + vrow * dm.m : nullptr;
-
   const int lane = tid % 64;
   const int l32 = lane % 32, hf = lane / 32;
-  const int64_t base = (int64_t)b * dm.sb + (int64_t)h * dm.sh;
-  const uint16_t* Qb = a.Q + base;
-  const uint16_t* Kb = a.K + base;
-  const uint16_t* Vtb = a.Vt + (size_t)bh * dm.m * D * BLK;
+  u32x4* lds = lds_all + grp * C::GROUP;
+
+  // ---- the items of this group, and how many rounds the workgroup turns -------------------
+  // Slots are numbered so that the 64 slots of one schedule queue sit on one XCD (workgroup id
+  // modulo 8) and the groups of a workgroup are neighbours in it.
+  const int n_wg = gridDim.x, wg = blockIdx.x;
+  auto slot_of_group = [&](int g) __attribute__((always_inline)) {
+    if (!sc.table) return wg * NGRP + g;
+    const int u = (wg / 8) * NGRP + g;
+    return ((wg % 8) + 8 * (u / 64)) * 64 + u % 64;
+  };
+  const int n_slots = n_wg * NGRP;                   // (index-order dealing)
+  auto record_of_item = [&](int i) __attribute__((always_inline)) {       // index order: dense items, then video rows
+    int bhx, qbx;
+    if (i < sc.n_dense) {
+      bhx = i / sc.dense_per_bh;
+      qbx = sc.dense_first + i % sc.dense_per_bh;
+    } else {
+      const int v = i - sc.n_dense;
+      bhx = v / dm.n;
+      qbx = v % dm.n;
+    }
+    return bhx * RSA_MAX_BLOCKS + qbx;
+  };
+  auto steps_of_record = [&](int rec) __attribute__((always_inline)) {
+    const int bhx = rec / RSA_MAX_BLOCKS, qbx = rec % RSA_MAX_BLOCKS;
+    const bool sp = !dense_all && qbx < dm.n;
+    return (sp ? list_length(a, dm, (size_t)bhx * dm.n + qbx) : dm.m) * C::SPB;
+  };
+  const int slot = slot_of_group(grp);
+  int n_my_items, wg_rounds = 0;
+  if (sc.table) {
+    n_my_items = sc.nitems[slot];
+#pragma unroll
+    for (int g = 0; g < NGRP; ++g) {
+      const int t = sc.total[slot_of_group(g)];
+      wg_rounds = max(wg_rounds, t > 0 ? t + 1 : 0);
+    }
+  } else {
+    n_my_items = slot < sc.n_items ? (sc.n_items - slot + n_slots - 1) / n_slots : 0;
+#pragma unroll
+    for (int g = 0; g < NGRP; ++g) {
+      int t = 0;
+      for (int i = wg * NGRP + g; i < sc.n_items; i += n_slots) t += steps_of_record(record_of_item(i));
+      wg_rounds = max(wg_rounds, t > 0 ? t + 1 : 0);
+    }
+  }
+  if (wg_rounds == 0) return;                        // the whole workgroup: nothing was dealt to it
+  auto my_record = [&](int k) __attribute__((always_inline)) {
+    typedef const int32_t __attribute__((address_space(4))) * const_i32_t;   // scalar loads
+    return sc.table ? ((const_i32_t)(uintptr_t)sc.table)[(size_t)slot * sc.cap + k] : record_of_item(slot + k * n_slots);
+  };
+
+  // What the phases need to know of an item: all wave-uniform.
+  typedef const int32_t __attribute__((address_space(4))) * const_list_t;
+  struct Item {
+    int bh, qb;
+    int ns;                 // steps: SPB per entry of its list (all M key blocks for a dense row)
+    int nlist;
+    int has_list;
+    const_list_t list;      // its list of key blocks; a dense row: any readable address
+    uint64_t Kbytes, Vtbytes;   // K rows and V^T tiles of its (batch, head)
+  };
+  auto load_item = [&](int k) __attribute__((always_inline)) {
+    Item it;
+    const int rec = my_record(k);
+    it.bh = rec / RSA_MAX_BLOCKS;
+    it.qb = rec % RSA_MAX_BLOCKS;
+    const bool sp = !dense_all && it.qb < dm.n;
+    const size_t vrow = (size_t)it.bh * dm.n + it.qb;
+    it.nlist = sp ? list_length(a, dm, vrow) : dm.m;
+    it.ns = it.nlist * C::SPB;
+    it.has_list = sp ? 1 : 0;
+    const int b = it.bh / dm.heads, h = it.bh % dm.heads;
+    const int64_t base = (int64_t)b * dm.sb + (int64_t)h * dm.sh;
+    // (with RSA_DENSE every list pointer may be NULL: a dense row reads the first word of Q instead)
+    it.list = (const_list_t)(uintptr_t)(sp ? (const void*)(a.block_idx + vrow * dm.m) : (const void*)a.Q);
+    it.Kbytes = (uint64_t)(uintptr_t)(a.K + base);
+    it.Vtbytes = (uint64_t)(uintptr_t)(a.Vt + (size_t)it.bh * dm.m * D * BLK);
+    return it;
+  };
 
   // ---- direct-to-LDS loads ---------------------------------------------------------------
   // A load fills 1 KB of LDS = RK consecutive K rows (RV consecutive V^T rows). Load ii of
@@ -213,21 +270,6 @@ __global__ __launch_bounds__(512, 1) void attn_kernel(Dims dm, AttnArgs a, int n
   const uint32_t ldsK_addr = (uint32_t)(uintptr_t)lds + wave * RK * (C::KCPR * 16);
   const uint32_t ldsV_addr = (uint32_t)(uintptr_t)lds + KSTAGES * KBUF * 16 + wave * RV * (C::VCPR * 16);
 
-  const int nsteps = nlist * C::SPB;
-  // The list is read through the constant address space: a scalar load, which neither waits
-  // for nor is held up by the direct-to-LDS loads in flight (a vector load would be both).
-  // A dense row has no list (with RSA_DENSE every list pointer may be NULL): its loads read the first
-  // word of Q instead, and the index itself is taken.
-  typedef const int32_t __attribute__((address_space(4))) * const_list_t;
-  const const_list_t clist = (const_list_t)(uintptr_t)(list ? (const void*)list : (const void*)Qb);   // Q: never NULL, at least one row long
-  const bool has_list = list != nullptr;
-  // entry j of the list; past its end the last entry again (a valid block: the tile requested for a
-  // step that does not exist is never read)
-  auto list_entry = [&](int j) __attribute__((always_inline)) {
-    j = min(j, nlist - 1);
-    const int e = clist[has_list ? j : 0];
-    return has_list ? e : j;
-  };
   // Requests for the K rows and the V^T rows of one step. Everything that does not depend on the
   // step is worked out once, in bytes: load ii of a wave is a per-lane byte offset (kvo / vvo, the
   // pass folded in) from the tile's scalar base and a constant LDS offset from the stage's scalar
@@ -238,8 +280,6 @@ __global__ __launch_bounds__(512, 1) void attn_kernel(Dims dm, AttnArgs a, int n
   const uint32_t kpass_bytes = (uint32_t)K_ROWS_PER_PASS * (uint32_t)dm.st * 2u;
   const int64_t text_adjust = ((int64_t)dm.tv - (int64_t)dm.n * BLK) * dm.st * 2;   // text blocks start at T_v, not N*B
   const int last_video_count = dm.block_count(dm.n - 1), last_count = dm.block_count(dm.m - 1);
-  const uint64_t Kbytes = (uint64_t)(uintptr_t)Kb;
-  const uint64_t Vtbytes = (uint64_t)(uintptr_t)Vtb;
   constexpr uint32_t kVtBlockBytes = (uint32_t)D * BLK * 2u;
   auto count_of = [&](int m) __attribute__((always_inline)) {
     int c = BLK;
@@ -270,7 +310,7 @@ __global__ __launch_bounds__(512, 1) void attn_kernel(Dims dm, AttnArgs a, int n
   // A ragged key block (the last video block, the last text block) adds vector work: K rows past
   // the block end re-read its last row (masked later; V^T is zero-padded in HBM), with per-lane
   // offsets from the start of the block.
-  auto open_block = [&](int m) __attribute__((always_inline)) {
+  auto open_block = [&](int m, uint64_t Kbytes, uint64_t Vtbytes) __attribute__((always_inline)) {
     blk_kp = Kbytes + ((uint64_t)(uint32_t)m * kblock_bytes + (uint64_t)(m >= dm.n ? text_adjust : 0));
     blk_vp = Vtbytes + (uint64_t)(uint32_t)m * kVtBlockBytes;
     blk_count = count_of(m);
@@ -296,13 +336,14 @@ __global__ __launch_bounds__(512, 1) void attn_kernel(Dims dm, AttnArgs a, int n
       kvw_ragged = 1;
     }
   };
-  auto issue_load = [&](const Tile& t, int idx) __attribute__((always_inline)) {
-    if (idx < C::KPW) {
-      const int ii = idx;
-      dma16_sv_at(t.kdst, (ii / KOFF) * K_LDS_PASS + (ii % KOFF) * K_LDS_CLASS, t.kp, kvw[ii], lds);
+  auto issue_load = [&](const Tile& t, auto idxc) __attribute__((always_inline)) {
+    constexpr int idx = decltype(idxc)::value;
+    if constexpr (idx < C::KPW) {
+      constexpr int ii = idx;
+      dma16_sv_imm<(ii / KOFF) * K_LDS_PASS + (ii % KOFF) * K_LDS_CLASS>(t.kdst, t.kp, kvw[ii], lds);
     } else {
-      const int ii = idx - C::KPW;
-      dma16_sv_at(t.vdst, (ii / VOFF) * V_LDS_PASS + (ii % VOFF) * V_LDS_CLASS, t.vp, vvo[ii], lds);
+      constexpr int ii = idx - C::KPW;
+      dma16_sv_imm<(ii / VOFF) * V_LDS_PASS + (ii % VOFF) * V_LDS_CLASS>(t.vdst, t.vp, vvo[ii], lds);
     }
   };
 
@@ -314,11 +355,20 @@ __global__ __launch_bounds__(512, 1) void attn_kernel(Dims dm, AttnArgs a, int n
 #pragma unroll
   for (int pc = 0; pc < C::PC; ++pc) vread[pc] = lds + KSTAGES * KBUF + swizzled<C::VCPR>(l32, 2 * pc + hf);
 
-  // ---- Q as the B operand of S^T = K Q^T, resident in registers --------------------------
-  const int q_count = dm.block_count(qb);
-  const int64_t q_t0 = dm.block_start(qb);
+  // ---- the item being computed, the one after it, and the one whose output is still to be written
+  Item cur = {}, nxt = {};
+  int nxt_valid = 0, k_next = 0;       // k_next: the first item not yet loaded
+  // what the epilogue needs of the item that has just ended
+  int done_bh = 0, done_qb = 0, done_sparse = 0;
+
+  // Q as the B operand of S^T = K Q^T, resident in registers; the next item's rows replace it right
+  // behind the last K Q^T of the current one.
   bf16x8 qreg[C::KS];
-  {
+  auto load_q = [&](const Item& it) __attribute__((always_inline)) {
+    const int b = it.bh / dm.heads, h = it.bh % dm.heads;
+    const uint16_t* Qb = a.Q + (int64_t)b * dm.sb + (int64_t)h * dm.sh;
+    const int q_count = dm.block_count(it.qb);
+    const int64_t q_t0 = dm.block_start(it.qb);
     const int q = wave * 32 + l32;
 #pragma unroll
     for (int s = 0; s < C::KS; ++s) {
@@ -326,11 +376,7 @@ __global__ __launch_bounds__(512, 1) void attn_kernel(Dims dm, AttnArgs a, int n
       if (q < q_count) v = *reinterpret_cast<const uint4*>(Qb + (q_t0 + q) * dm.st + 16 * s + 8 * hf);
       qreg[s] = __builtin_bit_cast(bf16x8, v);
     }
-    // Q must have arrived before the first direct-to-LDS load is requested: the compiler
-    // does not see those loads, and would otherwise place its own wait for Q -- a wait for
-    // *every* outstanding load -- at the first use inside the loop.
-    __builtin_amdgcn_s_waitcnt(0x0F70);
-  }
+  };
 
   floatx16 oacc[C::DT];
 #pragma unroll
@@ -340,20 +386,69 @@ __global__ __launch_bounds__(512, 1) void attn_kernel(Dims dm, AttnArgs a, int n
   float mref = -INFINITY, lpart = 0.f;   // softmax reference (log2 domain) and this lane's partial row sum
   const float cs = dm.scale * kLog2e;
 
+  // Epilogue of one item: O = R_n * acc / l + C_n (video rows; text rows: acc / l), bf16; then the
+  // running state starts over for the next item.
+  auto write_output = [&]() __attribute__((always_inline)) {
+    const int b = done_bh / dm.heads, h = done_bh % dm.heads;
+    const size_t vrow = (size_t)done_bh * dm.n + done_qb;      // row of the per-video-block tensors
+    const bool do_comp = done_sparse && (a.flags & RSA_COMPENSATE);
+    const float rfac = (done_sparse && (a.flags & RSA_RECTIFY_CRITICAL)) ? a.R[vrow] : 1.0f;
+    uint16_t* Ob = a.O + (int64_t)b * dm.sb + (int64_t)h * dm.sh;
+    const int q_count = dm.block_count(done_qb);
+    const int64_t q_t0 = dm.block_start(done_qb);
+    const float lsum = half_wave_sum(lpart);
+    const int q = wave * 32 + l32;
+    if (q < q_count) {
+      const float f = rfac / lsum;
+      uint16_t* orow = Ob + (q_t0 + q) * dm.st;
+      const float* crow = a.comp + vrow * D;     // C_n of this query block (only read when do_comp)
+#pragma unroll
+      for (int dt = 0; dt < C::DT; ++dt)
+#pragma unroll
+        for (int g = 0; g < 4; ++g) {
+          const int d0 = 32 * dt + 8 * g + 4 * hf;
+          float o[4];
+#pragma unroll
+          for (int e = 0; e < 4; ++e) o[e] = oacc[dt][4 * g + e] * f;
+          if (do_comp) {
+            const floatx4 c4 = *reinterpret_cast<const floatx4*>(crow + d0);
+#pragma unroll
+            for (int e = 0; e < 4; ++e) o[e] += c4[e];
+          }
+          uint2 w;
+          w.x = pack_bf16x2(o[0], o[1]);
+          w.y = pack_bf16x2(o[2], o[3]);
+          *reinterpret_cast<uint2*>(orow + d0) = w;
+        }
+      if (a.lse && hf == 0)
+        a.lse[((size_t)done_bh * dm.t) + q_t0 + q] = (mref + log2f(lsum)) * 0.6931471805599453f;
+    }
+#pragma unroll
+    for (int dt = 0; dt < C::DT; ++dt)
+#pragma unroll
+      for (int r = 0; r < 16; ++r) oacc[dt][r] = 0.f;
+    mref = -INFINITY;
+    lpart = 0.f;
+  };
+
   // Two groups of waves share every SIMD (wave w of group 0 and wave w of group 1). They run
   // the same sequence  [M(s) | barrier | V(s) | barrier] ...  one barrier apart, so that while
-  // one group issues MFMAs the other does its softmax on the VALU:
+  // one group issues MFMAs the other does its softmax on the VALU. s counts the steps of all the
+  // items of the group, one after the other without a gap:
   //   M(s): O^T += V^T P^T of step s-1, then S^T = K Q^T of step s: matrix instructions only, the A
-  //         operand of each read from LDS a fixed number of slots ahead (V^T tile of step s-1 from
-  //         its ring stage (s-1) % 3, K tile of step s from stage s % 2); the loads of tile s+1
-  //         (K into stage (s+1) % 2, V^T into stage (s+1) % 3) go out one per MFMA slot
-  //   V(s): mask, online softmax -> P as bf16 B operands (VALU only); fetch the list entry of step
-  //         s+2; wait for tile s+1; read the first V^T operands of M(s+1) ahead of the barrier
+  //         operand of each read from LDS a few slots ahead (V^T tile of step s-1 from its ring
+  //         stage (s-1) % 3, K tile of step s from stage s % 2); the loads of tile s+1 (K into
+  //         stage (s+1) % 2, V^T into stage (s+1) % 3) go out one per MFMA slot. Behind the last
+  //         step of an item the query rows of the next item are requested.
+  //   V(s): in the first step of an item, the output of the item before it; mask, online softmax
+  //         -> P as bf16 B operands (VALU only); fetch the list entry of step s+2; wait for tile
+  //         s+1; read the first V^T operands of M(s+1) ahead of the barrier
   // The barrier after V(s) publishes tile s+1 to the group. A K stage is rewritten two steps
   // after it was read, a V^T stage (read in M(s+1), one phase after its K tile) three steps after
   // it was filled: by then every wave of the group has passed the barrier that follows its last
-  // read.
-  int m_nxt = 0;          // key block of the step after the current one
+  // read. Every item has an even number of steps (SPB = 2 per key block), so the position inside a
+  // key block and the K stage both follow from the parity of s, which the unrolled loop knows.
+  int m_nxt = 0;          // key block that the next new-block step opens
   int kvc_cur = BLK;      // valid keys in the block of the current step
   int kvc_nxt = BLK;
   auto group_barrier = [&]() __attribute__((always_inline)) {
@@ -387,89 +482,116 @@ __global__ __launch_bounds__(512, 1) void attn_kernel(Dims dm, AttnArgs a, int n
     ring[slot % W] = __builtin_bit_cast(bf16x8, vcur[pc][dt * 32 * C::VCPR]);
   };
 
-  auto m_phase = [&](auto stc, auto pvc, auto qkc, int s) __attribute__((always_inline)) {
-    constexpr int ST = decltype(stc)::value;          // s modulo the unroll factor: gives the K stage and the part of the key block
-    constexpr bool do_pv = decltype(pvc)::value != 0, do_qk = decltype(qkc)::value != 0;
+  // Variants of the two phases, all compile-time:
+  //   MFMA phase  QK: 0 = the last P V product of the group alone.  LAST: the step is the last of its item
+  //               -- the tile of step s+1 may open the next item (that item's K and V^T), and the next
+  //               item's query rows are requested behind the last K Q^T.
+  //   softmax phase  FIRST: first step of an item (the output of the item before it is written first);
+  //               FETCH: 0 none (odd steps), 1 the next entry of the item's own list, 2 wherever step
+  //               s+2 falls (own list, first entry of the next item, or the last entry once more);
+  //               LAST: behind it the next item takes the place of the current one.
+  // The steps in the middle of an item run the plain variants in a loop of their own, so that what
+  // only the boundaries between items need stays out of its registers.
+  auto m_phase = [&](auto stc, auto qkc, auto lastc) __attribute__((always_inline)) {
+    constexpr int ST = decltype(stc)::value;          // s modulo 2: the K stage and the part of the key block
+    constexpr bool do_qk = decltype(qkc)::value != 0, last_of_item = decltype(lastc)::value != 0;
     constexpr int DSLOT = RSA_DSLOT;                  // the slot in which the requests for the next tile start
-    constexpr int LSTRIDE = RSA_LSTRIDE;              // ... and the slots from one request to the next
-    constexpr int FIRST = do_pv ? 0 : NPV, LAST = do_qk ? NSLOT : NPV;     // slots that hold an MFMA
+    constexpr int LAST = do_qk ? NSLOT : NPV;         // slots that hold an MFMA
     constexpr int WB = W / 2;                         // operands are waited for WB at a time
     Tile nt = {};
-    auto read_k_operand = [&](int slot) __attribute__((always_inline)) {   // slot >= NPV
-      const int q = slot - NPV, k2 = q / C::KT, t = q % C::KT;
-      ring[slot % W] = __builtin_bit_cast(bf16x8, kread[k2][(ST % KSTAGES) * KBUF + t * 32 * C::KCPR]);
-    };
-    auto read_operand = [&](int slot) __attribute__((always_inline)) {
-      if (slot < NPV) read_v_operand(slot); else read_k_operand(slot);
-    };
     // The wave that feeds the matrix pipe goes first wherever the two waves of a SIMD compete for an
     // issue slot: without this the older wave of the two wins, and the MFMA phases of the younger
     // group run a fifth longer than those of the other.
     __builtin_amdgcn_s_setprio(3);
-    if (!do_pv) {
-      // first step of a list: nothing was read ahead
-#pragma unroll
-      for (int j = FIRST; j < FIRST + W && j < LAST; ++j) read_operand(j);
-    }
     __builtin_amdgcn_sched_barrier(0);
-#pragma unroll
-    for (int i = FIRST; i < LAST; ++i) {
-      const int e = i - FIRST;                        // position among the MFMAs of this phase
+    static_for<0, LAST>([&](auto ic) __attribute__((always_inline)) {
+      constexpr int i = decltype(ic)::value;
       // The operands of slots i .. i+WB-1 have arrived once at most the reads behind them are
       // outstanding: one wait per WB slots, and none is needed in between.
-      if (e % WB == 0) {
-        const int behind = min(W - WB, max(LAST - i - WB, 0));
+      if constexpr (i % WB == 0) {
+        constexpr int behind = (LAST - i - WB) < 0 ? 0 : ((LAST - i - WB) < (W - WB) ? (LAST - i - WB) : (W - WB));
         // vmcnt and expcnt fields at "no wait", lgkmcnt = behind
-        if (behind == 0) __builtin_amdgcn_s_waitcnt(0xC07F);
-        else if (behind == 1) __builtin_amdgcn_s_waitcnt(0xC17F);
-        else if (behind == 2) __builtin_amdgcn_s_waitcnt(0xC27F);
-        else if (behind == 3) __builtin_amdgcn_s_waitcnt(0xC37F);
-        else __builtin_amdgcn_s_waitcnt(0xC47F);
+        __builtin_amdgcn_s_waitcnt(0xC07F | (behind << 8));
         __builtin_amdgcn_sched_barrier(0);
       }
       // one load of the tile of step s+1 per slot, behind the MFMA of the slot before
-      if (do_qk && e >= DSLOT && (e - DSLOT) % LSTRIDE == 0 && (e - DSLOT) / LSTRIDE < LPS) issue_load(nt, (e - DSLOT) / LSTRIDE);
-      if (i < NPV) {
-        const int pc = i / C::DT, dt = i % C::DT;
+      if constexpr (do_qk && i >= DSLOT && i - DSLOT < LPS) issue_load(nt, IntC<i - DSLOT>{});
+      if constexpr (i < NPV) {
+        constexpr int pc = i / C::DT, dt = i % C::DT;
         oacc[dt] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(ring[i % W], __builtin_bit_cast(bf16x8, pb[pc]), oacc[dt], 0, 0, 0);
       } else {
-        const int q = i - NPV, k2 = q / C::KT, t = q % C::KT;
+        constexpr int q = i - NPV, k2 = q / C::KT, t = q % C::KT;
         floatx16 c0 = sacc[t];
-        if (k2 == 0) {
+        if constexpr (k2 == 0) {
 #pragma unroll
           for (int r = 0; r < 16; ++r) c0[r] = 0.f;           // folds into the instruction's constant C operand
         }
         sacc[t] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(ring[i % W], qreg[k2], c0, 0, 0, 0);
       }
       // the ring entry this slot used takes the operand of slot i + W
-      if (i + W < LAST) read_operand(i + W);
-      if (do_qk && e < 2) {
+      if constexpr (i + W < LAST) {
+        constexpr int slot = i + W;
+        if constexpr (slot < NPV) {
+          read_v_operand(slot);
+        } else {
+          constexpr int q = slot - NPV, k2 = q / C::KT, t = q % C::KT;
+          ring[slot % W] = __builtin_bit_cast(bf16x8, kread[k2][(ST % KSTAGES) * KBUF + t * 32 * C::KCPR]);
+        }
+      }
+      if constexpr (do_qk && i < 2) {
         // behind the first MFMAs, so that the matrix pipe starts as soon as the barrier opens:
-        // addresses of the tile of step s+1. The loop is unrolled over the steps of a key block, so
-        // whether that step opens a new block (its list entry came in during V(s-1)) is known at
-        // compile time. A list that ends with this step requests the tile of its last entry once
-        // more, into a stage nobody reads again.
+        // addresses of the tile of step s+1. Whether that step opens a new key block (its list entry
+        // came in during V(s-1)) follows from the parity of s. A group whose last step this is
+        // requests the tile of its last list entry once more, into a stage nobody reads again.
         __builtin_amdgcn_sched_barrier(0);
         constexpr int PART_NEXT = (ST + 1) % C::SPB;
-        if (e == 0) {
-          if (PART_NEXT == 0) open_block(m_nxt);
+        if constexpr (i == 0) {
+          if constexpr (PART_NEXT == 0) {
+            const bool in_next = last_of_item && nxt_valid;
+            open_block(m_nxt, in_next ? nxt.Kbytes : cur.Kbytes, in_next ? nxt.Vtbytes : cur.Vtbytes);
+          }
           kvc_nxt = blk_count;
         } else {
           step_of_block(nt, PART_NEXT, (ST + 1) % KSTAGES, vst + 1 >= VSTAGES ? 0 : vst + 1);
         }
       }
       __builtin_amdgcn_sched_barrier(0);
-    }
-    // a phase with fewer slots than loads (the first step of a list has no P V product) sends the rest here
-#pragma unroll
-    for (int idx = 0; idx < LPS; ++idx) {
-      if (do_qk && DSLOT + idx * LSTRIDE >= LAST - FIRST) issue_load(nt, idx);
+    });
+    // a phase with fewer slots than loads sends the rest here
+    static_for<0, LPS>([&](auto ic) __attribute__((always_inline)) {
+      constexpr int idx = decltype(ic)::value;
+      if constexpr (do_qk && DSLOT + idx >= LAST) issue_load(nt, ic);
+    });
+    // behind the last K Q^T of an item: the query rows of the next one (they arrive before the end of
+    // the softmax phase, which waits for every load)
+    if constexpr (do_qk && last_of_item) {
+      if (nxt_valid) load_q(nxt);
     }
   };
 
-  auto v_phase = [&](auto stc, int s) __attribute__((always_inline)) {
+  // entry j of an item's list; a dense row: j itself
+  auto list_entry = [&](const Item& it, int j) __attribute__((always_inline)) {
+    const int e = it.list[it.has_list ? j : 0];
+    return it.has_list ? e : j;
+  };
+
+  int fj = 0;                 // entry of the current item's list that the next even step fetches
+  int have_output = 0;        // an item has ended and its output is still in the accumulators
+  auto v_phase = [&](auto stc, auto firstc, auto fetchc, auto lastc) __attribute__((always_inline)) {
     constexpr int ST = decltype(stc)::value;
+    constexpr bool first_of_item = decltype(firstc)::value != 0, last_of_item = decltype(lastc)::value != 0;
+    constexpr int FETCH = decltype(fetchc)::value;
     __builtin_amdgcn_s_setprio(0);
+    // the first step of an item: the P V products of the item before it are complete
+    // (tile s+1 is waited for first: the loads of the output would otherwise be waited for together
+    // with it at the end of the phase, and so would the stores, which now complete under the next
+    // MFMA phase)
+    if constexpr (first_of_item) {
+      if (have_output) {
+        __builtin_amdgcn_s_waitcnt(0x0F70);          // vmcnt(0)
+        write_output();
+      }
+    }
     {
       const int kv_count = kvc_cur;
       // accumulator register r of key tile t is key part*KVS + 32t + 8(r/4) + 4*hf + r%4 of the block
@@ -522,8 +644,18 @@ __global__ __launch_bounds__(512, 1) void attn_kernel(Dims dm, AttnArgs a, int n
       }
       lpart += rs;
     }
-    // the list entry of step s+2 (where that step opens a key block) for M(s+1), fetched a phase ahead
-    if ((ST + 2) % C::SPB == 0) m_nxt = list_entry((s + 2) / C::SPB);
+    // The list entry of step s+2 (an even step opens a key block) for M(s+1): fetched a phase ahead.
+    if constexpr (FETCH == 1) {
+      m_nxt = list_entry(cur, fj);
+      fj += 1;
+    } else if constexpr (FETCH == 2) {
+      // it may be the first entry of the next item; past the last item, the last entry again (a valid
+      // block: the tile requested for a step that does not exist is never read)
+      if (fj < cur.nlist) m_nxt = list_entry(cur, fj);
+      else if (nxt_valid) m_nxt = list_entry(nxt, 0);
+      else m_nxt = list_entry(cur, cur.nlist - 1);
+      fj += 1;
+    }
     kvc_cur = kvc_nxt;
     // the probabilities are complete here: nothing of the softmax may sink behind the barrier
     // into the MFMA phase, where it would take the other group's VALU time
@@ -536,97 +668,120 @@ __global__ __launch_bounds__(512, 1) void attn_kernel(Dims dm, AttnArgs a, int n
 #pragma unroll
     for (int j = 0; j < W; ++j) read_v_operand(j);
     vst = vst + 1 >= VSTAGES ? 0 : vst + 1;
-    // tile s+1 has landed (this wave's share; the barrier that follows covers the group)
-    __builtin_amdgcn_s_waitcnt(0x0F70);          // vmcnt(0)
+    if constexpr (last_of_item) {
+      // the item has ended: its output waits for the last P V product; the next item takes its place
+      done_bh = cur.bh;
+      done_qb = cur.qb;
+      done_sparse = cur.has_list;
+      have_output = 1;
+      if (nxt_valid) {
+        cur = nxt;
+        fj = 1;                          // entry 0 was fetched two steps ago
+        nxt_valid = k_next < n_my_items;
+        if (nxt_valid) nxt = load_item(k_next);
+        k_next += 1;
+      }
+    }
+    // tile s+1 has landed (this wave's share; the barrier that follows covers the group), and so
+    // have the query rows of the next item
+    if constexpr (first_of_item) {
+      if (!have_output) __builtin_amdgcn_s_waitcnt(0x0F70);
+    } else {
+      __builtin_amdgcn_s_waitcnt(0x0F70);          // vmcnt(0)
+    }
   };
 
-  if (nsteps > 0) {
+  const bool active = n_my_items > 0;
+  if (active) {
+    cur = load_item(0);
+    nxt_valid = n_my_items > 1;
+    if (nxt_valid) nxt = load_item(1);
+    k_next = 2;
+    load_q(cur);
+    // Q must have arrived before the first direct-to-LDS load is requested: the compiler
+    // does not see those loads, and would otherwise place its own wait for Q -- a wait for
+    // *every* outstanding load -- at the first use inside the loop.
+    __builtin_amdgcn_s_waitcnt(0x0F70);
     Tile t0;
-    open_block(list_entry(0));
+    open_block(list_entry(cur, 0), cur.Kbytes, cur.Vtbytes);
     step_of_block(t0, 0, 0, 0);
-#pragma unroll
-    for (int i = 0; i < LPS; ++i) issue_load(t0, i);
+    static_for<0, LPS>([&](auto ic) __attribute__((always_inline)) { issue_load(t0, ic); });
     kvc_cur = blk_count;
-    if (C::SPB == 1) m_nxt = list_entry(1);       // otherwise V(0) fetches it
+    fj = 1;
+    // The first MFMA phase multiplies the (zero) probabilities of a step that does not exist with
+    // whatever the last V^T stage holds: make that zeros too (0 x NaN would poison the accumulators).
+    {
+      u32x4* vlast = lds + KSTAGES * KBUF + (VSTAGES - 1) * C::VBUF;
+      for (int c = wave * 64 + lane; c < C::VBUF; c += C::NW * 64) vlast[c] = u32x4{0u, 0u, 0u, 0u};
+      // ... and the operands read ahead of it come from there
+#pragma unroll
+      for (int pc = 0; pc < C::PC; ++pc) vcur[pc] = vread[pc] + (VSTAGES - 1) * C::VBUF;
+    }
   }
   __builtin_amdgcn_s_waitcnt(0x0070);
-  group_barrier();                  // tile 0 of both groups is in LDS
+  group_barrier();                  // tile 0 of every group is in LDS
+  if (active) {
+#pragma unroll
+    for (int j = 0; j < W; ++j) read_v_operand(j);
+  }
   if (grp >= NGRP / 2) group_barrier();    // the second half of the groups runs one barrier behind the first
-  // Every group turns smax + 1 rounds of two barriers; a round is M(s), V(s) while the group has
-  // steps left, the last P V product alone in round nsteps, and nothing but the barriers after.
+  // Every group turns wg_rounds rounds of two barriers; round s is M(s), V(s) while the group has
+  // steps left, the last P V product and the last output in round my_total, and nothing but the
+  // barriers after.
   using Y = IntC<1>;
   using N = IntC<0>;
   int s = 0;
-  if (nsteps > 0) {
-    m_phase(IntC<0>{}, N{}, Y{}, 0);
-    group_barrier();
-    v_phase(IntC<0>{}, 0);
-    group_barrier();
-    s = 1;
-    while (s + 1 < nsteps) {        // s is odd here
-      m_phase(IntC<1>{}, Y{}, Y{}, s);
+  if (active) {
+    for (int item = 0; item < n_my_items; ++item) {
+      const int ns = cur.ns;
+      // step 0 of the item
+      m_phase(IntC<0>{}, Y{}, N{});
       group_barrier();
-      v_phase(IntC<1>{}, s);
+      v_phase(IntC<0>{}, Y{}, IntC<2>{}, N{});
       group_barrier();
-      m_phase(IntC<0>{}, Y{}, Y{}, s + 1);
+      if (ns >= 4) {
+        // steps 1 .. ns-4 in pairs: nothing but this item's own list and tiles
+        for (int sj = 1; sj + 3 < ns; sj += 2) {
+          m_phase(IntC<1>{}, Y{}, N{});
+          group_barrier();
+          v_phase(IntC<1>{}, N{}, IntC<0>{}, N{});
+          group_barrier();
+          m_phase(IntC<0>{}, Y{}, N{});
+          group_barrier();
+          v_phase(IntC<0>{}, N{}, IntC<1>{}, N{});
+          group_barrier();
+        }
+        // steps ns-3 and ns-2: the latter fetches the first list entry of the next item
+        m_phase(IntC<1>{}, Y{}, N{});
+        group_barrier();
+        v_phase(IntC<1>{}, N{}, IntC<0>{}, N{});
+        group_barrier();
+        m_phase(IntC<0>{}, Y{}, N{});
+        group_barrier();
+        v_phase(IntC<0>{}, N{}, IntC<2>{}, N{});
+        group_barrier();
+      }
+      // step ns-1
+      m_phase(IntC<1>{}, Y{}, Y{});
       group_barrier();
-      v_phase(IntC<0>{}, s + 1);
+      v_phase(IntC<1>{}, N{}, IntC<0>{}, Y{});
       group_barrier();
-      s += 2;
+      s += ns;
     }
-    if (s < nsteps) {
-      m_phase(IntC<1>{}, Y{}, Y{}, s);
-      group_barrier();
-      v_phase(IntC<1>{}, s);
-      group_barrier();
-      s += 1;
-    }
-    if (s & 1) m_phase(IntC<1>{}, Y{}, N{}, s); else m_phase(IntC<0>{}, Y{}, N{}, s);
+    m_phase(IntC<0>{}, N{}, N{});
     group_barrier();
+    __builtin_amdgcn_s_setprio(0);
+    write_output();
+    // nothing may be in flight into the LDS of a workgroup that is about to end
+    __builtin_amdgcn_s_waitcnt(0x0F70);
     group_barrier();
     s += 1;
   }
-  for (; s <= smax; ++s) {
+  for (; s < wg_rounds; ++s) {
     group_barrier();
     group_barrier();
   }
   if (grp < NGRP / 2) group_barrier();
-
-  if (!active) return;      // no barrier follows
-
-  // ---- epilogue: normalise, rectify, compensate, store ------------------------------------
-  const bool do_comp = sparse_row && (a.flags & RSA_COMPENSATE);
-  const float rfac = (sparse_row && (a.flags & RSA_RECTIFY_CRITICAL)) ? a.R[vrow] : 1.0f;
-  uint16_t* Ob = a.O + base;
-  {
-    const float lsum = half_wave_sum(lpart);
-    const int q = wave * 32 + l32;
-    if (q < q_count) {
-      const float f = rfac / lsum;
-      uint16_t* orow = Ob + (q_t0 + q) * dm.st;
-      const float* crow = a.comp + vrow * D;     // C_n of this query block (only read when do_comp)
-#pragma unroll
-      for (int dt = 0; dt < C::DT; ++dt)
-#pragma unroll
-        for (int g = 0; g < 4; ++g) {
-          const int d0 = 32 * dt + 8 * g + 4 * hf;
-          float o[4];
-#pragma unroll
-          for (int e = 0; e < 4; ++e) o[e] = oacc[dt][4 * g + e] * f;
-          if (do_comp) {
-            const floatx4 c4 = *reinterpret_cast<const floatx4*>(crow + d0);
-#pragma unroll
-            for (int e = 0; e < 4; ++e) o[e] += c4[e];
-          }
-          uint2 w;
-          w.x = pack_bf16x2(o[0], o[1]);
-          w.y = pack_bf16x2(o[2], o[3]);
-          *reinterpret_cast<uint2*>(orow + d0) = w;
-        }
-      if (a.lse && hf == 0)
-        a.lse[((size_t)bh * dm.t) + q_t0 + q] = (mref + log2f(lsum)) * 0.6931471805599453f;
-    }
-  }
 }
 
 // Pooled compensation (Alg. 1 step 21): C[n][:] = sum over blocks m that are not kept and
@@ -735,30 +890,173 @@ __global__ __launch_bounds__(1024) void row_order_kernel(Dims dm, AttnArgs a) {
   for (int i = tid; i < dm.n; i += 1024) a.row_order[(size_t)bh * dm.n + i] = (int32_t)(keys[i] & 4095u);
 }
 
+// Deals the items of one launch to the slots of the persistent attention kernel. One workgroup per
+// queue of 64 slots (the slots of a queue run on one XCD). The queue's items, in launch order: its
+// share of the dense items (text query blocks, or every block under RSA_DENSE: the long ones first),
+// then, head by head, its contiguous range of the row order of the video query blocks. They are
+// dealt in rounds by one wave, lane = slot: in a round every slot whose load (steps so far) is within
+// one item of the lightest takes the next item, in lane order -- neighbouring items go to neighbouring
+// slots at about the same time, so that workgroups resident together walk similar lists, and the
+// loads end within one item of each other whatever the lengths of the rows.
+// Minimum over the 64 lanes of a wave with data-parallel-primitive moves (row shifts inside the rows of
+// 16 lanes, then the two row broadcasts): lane 63 ends up with it. Lanes without a source take INT_MAX.
+__device__ __forceinline__ int wave_min_i32(int v) {
+  constexpr int kMax = 0x7fffffff;
+  v = min(v, __builtin_amdgcn_update_dpp(kMax, v, 0x111, 0xf, 0xf, false));   // row_shr:1
+  v = min(v, __builtin_amdgcn_update_dpp(kMax, v, 0x112, 0xf, 0xf, false));   // row_shr:2
+  v = min(v, __builtin_amdgcn_update_dpp(kMax, v, 0x114, 0xf, 0xf, false));   // row_shr:4
+  v = min(v, __builtin_amdgcn_update_dpp(kMax, v, 0x118, 0xf, 0xf, false));   // row_shr:8
+  v = min(v, __builtin_amdgcn_update_dpp(kMax, v, 0x142, 0xa, 0xf, false));   // row_bcast:15 into rows 1 and 3
+  v = min(v, __builtin_amdgcn_update_dpp(kMax, v, 0x143, 0xc, 0xf, false));   // row_bcast:31 into rows 2 and 3
+  return __builtin_amdgcn_readlane(v, 63);
+}
+
+struct DealArgs {
+  int32_t* table;           // [queues * 64][cap]
+  int32_t* nitems;          // [queues * 64]
+  int32_t* total;           // [queues * 64]
+  int cap, n_queues, slots_per_xcd;
+  int n_dense, dense_per_bh, dense_first;
+};
+template <int SPB>
+__global__ __launch_bounds__(256) void schedule_kernel(Dims dm, AttnArgs a, DealArgs da) {
+  constexpr int SEG = 2048;
+  constexpr int kStrictTail = 128;
+  __shared__ int32_t rec[SEG], len[SEG];
+  const int q = blockIdx.x, tid = threadIdx.x, lane = tid % 64;
+  const bool dense_all = (a.flags & RSA_DENSE) != 0;
+  const int bh_total = dm.batch * dm.heads;
+  // items of this queue: dense items d = q, q + n_queues, ...; then for every head the positions
+  // [q N / n_queues, (q + 1) N / n_queues) of its row order
+  const int my_dense = q < da.n_dense ? (da.n_dense - q + da.n_queues - 1) / da.n_queues : 0;
+  const int p0 = (int)((long long)q * dm.n / da.n_queues), p1 = (int)((long long)(q + 1) * dm.n / da.n_queues);
+  const int per_head = dense_all ? 0 : p1 - p0;
+  const int n_queue_items = my_dense + per_head * bh_total;
+  // lane = slot u of this queue; the XCD has slots_per_xcd of them in all
+  const bool slot_ok = (q / 8) * 64 + lane < da.slots_per_xcd;
+  const int slot = q * 64 + lane;
+  int load = 0, cnt = 0;
+  for (int seg0 = 0; seg0 < n_queue_items; seg0 += SEG) {
+    const int seg_n = min(SEG, n_queue_items - seg0);
+    __syncthreads();
+    for (int i = tid; i < seg_n; i += 256) {
+      const int it = seg0 + i;
+      int bhx, qbx;
+      if (it < my_dense) {
+        const int d = q + it * da.n_queues;
+        bhx = d / da.dense_per_bh;
+        qbx = da.dense_first + d % da.dense_per_bh;
+      } else {
+        const int v = it - my_dense;
+        bhx = v / per_head;
+        const int pos = p0 + v % per_head;
+        qbx = a.row_order ? a.row_order[(size_t)bhx * dm.n + pos] : pos;
+      }
+      const bool sp = !dense_all && qbx < dm.n;
+      rec[i] = bhx * RSA_MAX_BLOCKS + qbx;
+      len[i] = (sp ? list_length(a, dm, (size_t)bhx * dm.n + qbx) : dm.m) * SPB;
+    }
+    __syncthreads();
+    if (tid < 64) {
+      int next = 0;
+      while (next < seg_n) {
+        const bool can = slot_ok && cnt < da.cap;
+        const int lightest = wave_min_i32(can ? load : 0x7fffffff);
+        bool take = can && load < lightest + len[next];
+        if (n_queue_items - (seg0 + next) <= kStrictTail) {
+          // the last items go one at a time to the lightest slot, so that the loads end within one item
+          const unsigned long long lightest_ones = __ballot(can && load == lightest);
+          take = lightest_ones != 0 && lane == __builtin_ctzll(lightest_ones);
+        }
+        const unsigned long long takers = __ballot(take);
+        const int mine = next + __builtin_amdgcn_mbcnt_hi((uint32_t)(takers >> 32), __builtin_amdgcn_mbcnt_lo((uint32_t)takers, 0));
+        if (take && mine < seg_n) {
+          da.table[(size_t)slot * da.cap + cnt] = rec[mine];
+          load += len[mine];
+          cnt += 1;
+        }
+        if (takers == 0) break;            // cannot happen while the table has room (the lightest slot always takes)
+        next += __popcll(takers);
+      }
+    }
+  }
+  if (tid < 64) {
+    da.nitems[slot] = cnt;
+    da.total[slot] = load;
+  }
+}
+
+// Sizes of the schedule for `n_wg` resident workgroups of NGRP groups (host and launcher agree on them).
+struct SchedShape {
+  int n_queues, slots_per_xcd, cap, chunk, n_items, n_dense, dense_per_bh, dense_first;
+};
+inline SchedShape sched_shape(const Dims& dm, int flags, int n_wg, int ngrp) {
+  SchedShape s;
+  const bool dense_all = (flags & RSA_DENSE) != 0;
+  const int bh = dm.batch * dm.heads;
+  s.slots_per_xcd = (n_wg / 8) * ngrp;
+  s.n_queues = 8 * ((s.slots_per_xcd + 63) / 64);
+  s.dense_per_bh = dense_all ? dm.m : dm.mt;
+  s.dense_first = dense_all ? 0 : dm.n;
+  s.n_dense = bh * s.dense_per_bh;
+  s.n_items = s.n_dense + (dense_all ? 0 : bh * dm.n);
+  s.chunk = (dm.n + s.n_queues - 1) / s.n_queues;
+  const long long longest = (s.n_dense + s.n_queues - 1) / s.n_queues + (dense_all ? 0LL : (long long)bh * s.chunk);
+  // room for twice the average share of a slot, so that a queue of very unequal items still balances;
+  // the last queue of an XCD may have fewer than 64 slots
+  const int fewest = s.slots_per_xcd % 64 ? s.slots_per_xcd % 64 : 64;
+  s.cap = (int)(2 * ((longest + fewest - 1) / fewest) + 8);
+  return s;
+}
+
 template <int D, int BLK>
-hipError_t launch_attn_t(const Dims& dm, const AttnArgs& a, hipStream_t s) {
+hipError_t launch_attn_t(const Dims& dm, const AttnArgs& a, const AttnSched& ws, hipStream_t s) {
   using C = AttnCfg<D, BLK>;
   const int bh = dm.batch * dm.heads;
   const bool dense_all = (a.flags & RSA_DENSE) != 0;
-  constexpr int G = C::NGRP;                                                       // query blocks per workgroup
-  const int n_text_items = bh * (((dense_all ? dm.m : dm.mt) + G - 1) / G);       // workgroups of dense rows
-  const int chunk = (dm.n + 7) / 8;
-  const long long grid = (long long)n_text_items + (dense_all ? 0 : (long long)bh * 8 * ((chunk + G - 1) / G));
-  if (grid <= 0 || grid > 0x7fffffffLL) return hipErrorInvalidValue;
+  const int n_wg = ws.n_wg;
+  if (n_wg < 8 || n_wg % 8) return hipErrorInvalidValue;
+  const SchedShape sh = sched_shape(dm, a.flags, n_wg, C::NGRP);
+  SchedArgs sc = {};
+  sc.n_items = sh.n_items;
+  sc.n_dense = sh.n_dense;
+  sc.dense_per_bh = sh.dense_per_bh > 0 ? sh.dense_per_bh : 1;
+  sc.dense_first = sh.dense_first;
   if (!dense_all && (a.flags & RSA_COMPENSATE))
     hipLaunchKernelGGL((compensation_kernel<D>), dim3((dm.n + 3) / 4, bh), dim3(256), 0, s, dm, a);
   if (!dense_all && a.row_order) hipLaunchKernelGGL(row_order_kernel, dim3(bh), dim3(1024), 0, s, dm, a);
-  hipLaunchKernelGGL((attn_kernel<D, BLK>), dim3((unsigned)grid), dim3(C::NTHR), 0, s, dm, a, n_text_items, chunk);
+  if (ws.table && sh.n_queues * 64 <= RSA_ATTN_SCHED_SLOTS && (size_t)sh.n_queues * 64 * sh.cap <= ws.table_entries) {
+    DealArgs da;
+    da.table = ws.table; da.nitems = ws.nitems; da.total = ws.total;
+    da.cap = sh.cap; da.n_queues = sh.n_queues; da.slots_per_xcd = sh.slots_per_xcd;
+    da.n_dense = sh.n_dense; da.dense_per_bh = sc.dense_per_bh; da.dense_first = sh.dense_first;
+    hipLaunchKernelGGL((schedule_kernel<C::SPB>), dim3(sh.n_queues), dim3(256), 0, s, dm, a, da);
+    sc.table = ws.table; sc.nitems = ws.nitems; sc.total = ws.total; sc.cap = sh.cap;
+  }
+  hipLaunchKernelGGL((attn_kernel<D, BLK>), dim3((unsigned)n_wg), dim3(C::NTHR), 0, s, dm, a, sc);
   return hipGetLastError();
 }
 
 }  // namespace
 
-hipError_t launch_attn(const Dims& dm, const AttnArgs& a, hipStream_t s) {
-  if (dm.d == 128 && dm.blk == 128) return launch_attn_t<128, 128>(dm, a, s);
-  if (dm.d == 128 && dm.blk == 64) return launch_attn_t<128, 64>(dm, a, s);
-  if (dm.d == 64 && dm.blk == 128) return launch_attn_t<64, 128>(dm, a, s);
-  return launch_attn_t<64, 64>(dm, a, s);
+// Entries of the schedule table for RSA_ATTN_MAX_WGS resident workgroups, dense launch or not. (A GPU
+// with fewer CUs forms fewer, longer queues; should its table not fit, the items go out in index order.)
+size_t attn_sched_entries(const Dims& dm) {
+  const int ngrp = dm.blk == 128 ? 2 : 4;
+  size_t need = 0;
+  for (int flags : {0, (int)RSA_DENSE}) {
+    const SchedShape sh = sched_shape(dm, flags, RSA_ATTN_MAX_WGS, ngrp);
+    const size_t e = (size_t)sh.n_queues * 64 * (size_t)sh.cap;
+    need = e > need ? e : need;
+  }
+  return need;
+}
+
+hipError_t launch_attn(const Dims& dm, const AttnArgs& a, const AttnSched& ws, hipStream_t s) {
+  if (dm.d == 128 && dm.blk == 128) return launch_attn_t<128, 128>(dm, a, ws, s);
+  if (dm.d == 128 && dm.blk == 64) return launch_attn_t<128, 64>(dm, a, ws, s);
+  if (dm.d == 64 && dm.blk == 128) return launch_attn_t<64, 128>(dm, a, ws, s);
+  return launch_attn_t<64, 64>(dm, a, ws, s);
 }
 
 }  // namespace rsa

@@ -27,6 +27,12 @@ __device__ __forceinline__ void dma16_sv_at(uint32_t lds_base, uint32_t lds_off,
   asm volatile("s_add_u32 m0, %0, %1\n\tglobal_load_lds_dwordx4 %2, %3"
                ::"s"(lds_base), "s"(lds_off), "v"(voff), "s"(sbase), "r"(fence) : "memory", "scc");
 }
+// ... and with the offset as a literal of the instruction (no register held for it).
+template <uint32_t LDS_OFF>
+__device__ __forceinline__ void dma16_sv_imm(uint32_t lds_base, uint64_t sbase, uint32_t voff, void* fence) {
+  asm volatile("s_add_u32 m0, %0, %1\n\tglobal_load_lds_dwordx4 %2, %3"
+               ::"s"(lds_base), "n"(LDS_OFF), "v"(voff), "s"(sbase), "r"(fence) : "memory", "scc");
+}
 __device__ __forceinline__ void dma16_v(uint32_t lds_addr, const void* gptr, void* fence) {
   asm volatile("s_mov_b32 m0, %0\n\tglobal_load_lds_dwordx4 %1, off"
                ::"s"(__builtin_amdgcn_readfirstlane(lds_addr)), "v"(gptr), "r"(fence) : "memory");

@@ -61,13 +61,41 @@ PoolWs pool_ws_layout(const Dims& d) {
   return w;
 }
 
-// rsa_sparse_attn_rectified scratch: the pooled compensation term C_n, fp32 [b][h][N][d], then
-// the launch order of the video query blocks, int32 [b][h][N].
-size_t attn_ws_comp_bytes(const Dims& d) {
-  return align256((size_t)d.batch * d.heads * d.n * d.d * sizeof(float));
+// rsa_sparse_attn_rectified scratch: the pooled compensation term C_n, fp32 [b][h][N][d]; the launch
+// order of the video query blocks, int32 [b][h][N]; the schedule of the persistent kernel (item
+// table, items and steps per slot).
+struct AttnWs {
+  size_t comp, order, table, nitems, total, bytes;
+  size_t table_entries;
+};
+AttnWs attn_ws_layout(const Dims& d) {
+  AttnWs w;
+  size_t off = 0;
+  w.comp = off;   off += align256((size_t)d.batch * d.heads * d.n * d.d * sizeof(float));
+  w.order = off;  off += align256((size_t)d.batch * d.heads * d.n * sizeof(int32_t));
+  w.table_entries = rsa::attn_sched_entries(d);
+  w.table = off;  off += align256(w.table_entries * sizeof(int32_t));
+  w.nitems = off; off += align256(RSA_ATTN_SCHED_SLOTS * sizeof(int32_t));
+  w.total = off;  off += align256(RSA_ATTN_SCHED_SLOTS * sizeof(int32_t));
+  w.bytes = off;
+  return w;
 }
-size_t attn_ws_size(const Dims& d) {
-  return attn_ws_comp_bytes(d) + align256((size_t)d.batch * d.heads * d.n * sizeof(int32_t));
+size_t attn_ws_size(const Dims& d) { return attn_ws_layout(d).bytes; }
+
+// Workgroups of the persistent attention kernel: one per CU of the current device, in whole
+// multiples of the 8 XCDs, at most RSA_ATTN_MAX_WGS. The CU count is read once per device.
+constexpr int kMaxDevices = 64;
+std::atomic<int> g_cu_count[kMaxDevices];
+int attn_workgroups() {
+  int dev = 0;
+  if (hipGetDevice(&dev) != hipSuccess || dev < 0 || dev >= kMaxDevices) return 0;
+  int cus = g_cu_count[dev].load(std::memory_order_acquire);
+  if (cus == 0) {
+    if (hipDeviceGetAttribute(&cus, hipDeviceAttributeMultiprocessorCount, dev) != hipSuccess || cus < 8) return 0;
+    g_cu_count[dev].store(cus, std::memory_order_release);
+  }
+  int n = cus < RSA_ATTN_MAX_WGS ? cus : RSA_ATTN_MAX_WGS;
+  return n - n % 8;
 }
 
 // Argument checks shared by the two attention entry points. RSA_DENSE drops the other flags.
@@ -93,10 +121,22 @@ int enqueue_attn(const Dims& d, const void* Q, const void* K, const void* Vt, co
   rsa::AttnArgs aa;
   aa.Q = (const uint16_t*)Q; aa.K = (const uint16_t*)K; aa.Vt = (const uint16_t*)Vt;
   aa.block_idx = block_idx; aa.count = count; aa.mask_bits = mask_bits; aa.Mc_bits = Mc_bits;
-  aa.R = R; aa.Apool = Apool; aa.Vp = Vp; aa.O = (uint16_t*)O; aa.lse = lse; aa.comp = (float*)ws;
-  aa.row_order = (ws && !(flags & RSA_DENSE)) ? (int32_t*)((char*)ws + attn_ws_comp_bytes(d)) : nullptr;
+  aa.R = R; aa.Apool = Apool; aa.Vp = Vp; aa.O = (uint16_t*)O; aa.lse = lse;
   aa.flags = flags;
-  if (rsa::launch_attn(d, aa, (hipStream_t)stream) != hipSuccess) return RSA_E_LAUNCH;
+  rsa::AttnSched sch = {};
+  sch.n_wg = attn_workgroups();
+  if (sch.n_wg < 8) return RSA_E_LAUNCH;
+  char* wsb = (char*)ws;
+  const AttnWs wl = attn_ws_layout(d);
+  aa.comp = ws ? (float*)(wsb + wl.comp) : nullptr;
+  aa.row_order = (ws && !(flags & RSA_DENSE)) ? (int32_t*)(wsb + wl.order) : nullptr;
+  if (ws) {
+    sch.table = (int32_t*)(wsb + wl.table);
+    sch.nitems = (int32_t*)(wsb + wl.nitems);
+    sch.total = (int32_t*)(wsb + wl.total);
+    sch.table_entries = wl.table_entries;
+  }
+  if (rsa::launch_attn(d, aa, sch, (hipStream_t)stream) != hipSuccess) return RSA_E_LAUNCH;
   return RSA_OK;
 }
 
@@ -105,7 +145,6 @@ int enqueue_attn(const Dims& d, const void* Q, const void* K, const void* Vt, co
 // handle for hipGetSymbolAddress; the device address it yields (one per device) is what kernels get.
 __attribute__((used)) static __device__ __align__(256) unsigned char scratch[RSA_STATIC_SCRATCH_BYTES];
 
-constexpr int kMaxDevices = 64;
 std::atomic<void*> g_scratch_ptr[kMaxDevices];
 
 void* static_scratch_of_current_device() {
@@ -254,6 +293,8 @@ int rsa_sparse_attn_rectified(const rsa_shape* shape, const void* Q, const void*
   if (!(flags & RSA_DENSE)) {
     if ((flags & RSA_COMPENSATE) && !ws) return RSA_E_NULL;
     if (ws && (ws_bytes < attn_ws_size(d) || ((uintptr_t)ws & 255))) return RSA_E_WORKSPACE;
+  } else if (ws && (ws_bytes < attn_ws_size(d) || ((uintptr_t)ws & 255))) {
+    ws = nullptr;            // a dense launch never needed a workspace: without a usable one it runs in index order
   }
   return enqueue_attn(d, Q, K, Vt, block_idx, count, mask_bits, R, Apool, Mc_bits, Vp, flags, O, lse, ws, stream);
 }

@@ -121,6 +121,16 @@ struct AttnArgs {
   int32_t* row_order;      // workspace [b][h][N]: launch order of the video query blocks (NULL: natural)
   int flags;
 };
-hipError_t launch_attn(const Dims& dm, const AttnArgs& a, hipStream_t s);
+// Persistent attention kernel: number of resident workgroups and (optional) room for its schedule.
+#define RSA_ATTN_MAX_WGS 256
+struct AttnSched {
+  int n_wg;                 // workgroups to launch: a multiple of 8, at most RSA_ATTN_MAX_WGS
+  int32_t* table;           // NULL: items are dealt in index order
+  int32_t *nitems, *total;  // [RSA_ATTN_SCHED_SLOTS] each
+  size_t table_entries;     // room in `table`
+};
+#define RSA_ATTN_SCHED_SLOTS 4096
+size_t attn_sched_entries(const Dims& dm);   // table entries that rsa_workspace_bytes sets aside
+hipError_t launch_attn(const Dims& dm, const AttnArgs& a, const AttnSched& ws, hipStream_t s);
 
 }  // namespace rsa
