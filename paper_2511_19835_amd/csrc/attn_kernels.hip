@@ -49,6 +49,7 @@ constexpr int VSTAGES = 3;           // ... of its V^T tiles, which are read one
 #ifndef RSA_DSLOT
 #define RSA_DSLOT 2
 #endif
+constexpr bool SPLIT_LOADS = true;   // K rows requested in the MFMA phase, V^T rows in the softmax phase
 constexpr int MWIN = RSA_MWIN;      // MFMA slots between the LDS read of a K operand and its use
 
 template <int D, int BLK>
@@ -108,10 +109,11 @@ __device__ __forceinline__ float half_wave_sum(float v) {
   return lo + hi;
 }
 
-// The running softmax reference is only raised when a row's new maximum exceeds it by
-// more than this many binades; probabilities then stay below 2^kLazyBits, which fp32 sums
-// and bf16 operands hold without loss, and the accumulators are rescaled rarely.
-constexpr float kLazyBits = 6.0f;
+// The running softmax reference only moves when a score is more than this many binades away from it
+// (above it; in the first step of an item, either way): probabilities then stay within 2^+-kLazyBits of
+// one another's scale, far inside what fp32 sums and bf16 operands hold, and the accumulators are
+// rescaled very rarely.
+constexpr float kLazyBits = 40.0f;
 
 template <int V>
 struct IntC { static constexpr int value = V; };
@@ -364,6 +366,7 @@ __global__ __launch_bounds__(512, 1) void attn_kernel(Dims dm, AttnArgs a, Sched
   // Q as the B operand of S^T = K Q^T, resident in registers; the next item's rows replace it right
   // behind the last K Q^T of the current one.
   bf16x8 qreg[C::KS];
+  const float cs = dm.scale * kLog2e;   // scores -> binades
   auto load_q = [&](const Item& it) __attribute__((always_inline)) {
     const int b = it.bh / dm.heads, h = it.bh % dm.heads;
     const uint16_t* Qb = a.Q + (int64_t)b * dm.sb + (int64_t)h * dm.sh;
@@ -377,14 +380,12 @@ __global__ __launch_bounds__(512, 1) void attn_kernel(Dims dm, AttnArgs a, Sched
       qreg[s] = __builtin_bit_cast(bf16x8, v);
     }
   };
-
   floatx16 oacc[C::DT];
 #pragma unroll
   for (int dt = 0; dt < C::DT; ++dt)
 #pragma unroll
     for (int r = 0; r < 16; ++r) oacc[dt][r] = 0.f;
-  float mref = -INFINITY, lpart = 0.f;   // softmax reference (log2 domain) and this lane's partial row sum
-  const float cs = dm.scale * kLog2e;
+  float mref = 0.f, lpart = 0.f;         // softmax reference (log2 domain) and this lane's partial row sum
 
   // Epilogue of one item: O = R_n * acc / l + C_n (video rows; text rows: acc / l), bf16; then the
   // running state starts over for the next item.
@@ -427,7 +428,7 @@ __global__ __launch_bounds__(512, 1) void attn_kernel(Dims dm, AttnArgs a, Sched
     for (int dt = 0; dt < C::DT; ++dt)
 #pragma unroll
       for (int r = 0; r < 16; ++r) oacc[dt][r] = 0.f;
-    mref = -INFINITY;
+    mref = 0.f;
     lpart = 0.f;
   };
 
@@ -474,6 +475,7 @@ __global__ __launch_bounds__(512, 1) void attn_kernel(Dims dm, AttnArgs a, Sched
 #pragma unroll
   for (int i = 0; i < W; ++i) ring[i] = __builtin_bit_cast(bf16x8, u32x4{0u, 0u, 0u, 0u});
   int vst = 0;                // V^T ring stage of the current step (s % VSTAGES)
+  Tile vt_next = {};          // the tile of step s+1 as M(s) prepared it: its V^T rows are requested in V(s)
   const u32x4* vcur[C::PC];   // vread[] moved to the V^T stage whose P V product comes next
 #pragma unroll
   for (int pc = 0; pc < C::PC; ++pc) vcur[pc] = vread[pc];
@@ -496,6 +498,7 @@ __global__ __launch_bounds__(512, 1) void attn_kernel(Dims dm, AttnArgs a, Sched
     constexpr int ST = decltype(stc)::value;          // s modulo 2: the K stage and the part of the key block
     constexpr bool do_qk = decltype(qkc)::value != 0, last_of_item = decltype(lastc)::value != 0;
     constexpr int DSLOT = RSA_DSLOT;                  // the slot in which the requests for the next tile start
+    constexpr int MLOADS = SPLIT_LOADS ? C::KPW : LPS;   // requests of this phase: the K rows, or the whole tile
     constexpr int LAST = do_qk ? NSLOT : NPV;         // slots that hold an MFMA
     constexpr int WB = W / 2;                         // operands are waited for WB at a time
     Tile nt = {};
@@ -515,7 +518,7 @@ __global__ __launch_bounds__(512, 1) void attn_kernel(Dims dm, AttnArgs a, Sched
         __builtin_amdgcn_sched_barrier(0);
       }
       // one load of the tile of step s+1 per slot, behind the MFMA of the slot before
-      if constexpr (do_qk && i >= DSLOT && i - DSLOT < LPS) issue_load(nt, IntC<i - DSLOT>{});
+      if constexpr (do_qk && i >= DSLOT && i - DSLOT < MLOADS) issue_load(nt, IntC<i - DSLOT>{});
       if constexpr (i < NPV) {
         constexpr int pc = i / C::DT, dt = i % C::DT;
         oacc[dt] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(ring[i % W], __builtin_bit_cast(bf16x8, pb[pc]), oacc[dt], 0, 0, 0);
@@ -558,10 +561,15 @@ __global__ __launch_bounds__(512, 1) void attn_kernel(Dims dm, AttnArgs a, Sched
       __builtin_amdgcn_sched_barrier(0);
     });
     // a phase with fewer slots than loads sends the rest here
-    static_for<0, LPS>([&](auto ic) __attribute__((always_inline)) {
+    static_for<0, MLOADS>([&](auto ic) __attribute__((always_inline)) {
       constexpr int idx = decltype(ic)::value;
       if constexpr (do_qk && DSLOT + idx >= LAST) issue_load(nt, ic);
     });
+    if constexpr (do_qk) vt_next = nt;
+    if constexpr (SPLIT_LOADS) {
+      // the V^T rows of this step (requested a phase ago, ahead of this phase's K rows) have landed
+      wait_loads_leaving<do_qk ? MLOADS : 0>();
+    }
     // behind the last K Q^T of an item: the query rows of the next one (they arrive before the end of
     // the softmax phase, which waits for every load)
     if constexpr (do_qk && last_of_item) {
@@ -582,6 +590,10 @@ __global__ __launch_bounds__(512, 1) void attn_kernel(Dims dm, AttnArgs a, Sched
     constexpr bool first_of_item = decltype(firstc)::value != 0, last_of_item = decltype(lastc)::value != 0;
     constexpr int FETCH = decltype(fetchc)::value;
     __builtin_amdgcn_s_setprio(0);
+    constexpr int VLOADS = SPLIT_LOADS ? C::VPW : 0;  // requests of this phase: the V^T rows of step s+1
+    if constexpr (SPLIT_LOADS && !first_of_item) {
+      static_for<0, C::VPW>([&](auto ic) __attribute__((always_inline)) { issue_load(vt_next, IntC<C::KPW + decltype(ic)::value>{}); });
+    }
     // the first step of an item: the P V products of the item before it are complete
     // (tile s+1 is waited for first: the loads of the output would otherwise be waited for together
     // with it at the end of the phase, and so would the stores, which now complete under the next
@@ -590,6 +602,9 @@ __global__ __launch_bounds__(512, 1) void attn_kernel(Dims dm, AttnArgs a, Sched
       if (have_output) {
         __builtin_amdgcn_s_waitcnt(0x0F70);          // vmcnt(0)
         write_output();
+      }
+      if constexpr (SPLIT_LOADS) {
+        static_for<0, C::VPW>([&](auto ic) __attribute__((always_inline)) { issue_load(vt_next, IntC<C::KPW + decltype(ic)::value>{}); });
       }
     }
     {
@@ -606,40 +621,69 @@ __global__ __launch_bounds__(512, 1) void attn_kernel(Dims dm, AttnArgs a, Sched
           }
       }
       // ---- online softmax, one query column per lane ---------------------------------
+      // Scores are counted in binades (score * scale * log2 e). The reference stays 0 -- the
+      // probabilities are then exp2 of the scaled score itself -- unless the first step of an item
+      // sees a score more than kLazyBits binades away from 0, or a later step one that far above the
+      // reference: fp32 sums and bf16 operands span 2^+-126, so nothing overflows or vanishes inside
+      // that window, and weights that far below the row maximum do not matter to any digit kept.
       float mx = -INFINITY;
 #pragma unroll
       for (int t = 0; t < C::KT; ++t)
 #pragma unroll
         for (int r = 0; r < 16; ++r) mx = fmaxf(mx, sacc[t][r]);
-      mx = half_wave_max(mx) * cs;
-      if (__any(mx > mref + kLazyBits)) {
-        const float mnew = fmaxf(mref, mx);
-        const float alpha = __builtin_amdgcn_exp2f(mref - mnew);
-        mref = mnew;
-        lpart *= alpha;
+      mx = half_wave_max(mx) * cs;                     // the scale is positive
+      if constexpr (first_of_item) {
+        if (__any(fabsf(mx) > kLazyBits)) mref = mx;     // accumulators and row sum are empty: nothing to rescale
+      } else {
+        if (__any(mx > mref + kLazyBits)) {
+          const float mnew = fmaxf(mref, mx);
+          const float alpha = __builtin_amdgcn_exp2f(mref - mnew);
+          mref = mnew;
+          lpart *= alpha;
 #pragma unroll
-        for (int dt = 0; dt < C::DT; ++dt)
+          for (int dt = 0; dt < C::DT; ++dt)
 #pragma unroll
-          for (int r = 0; r < 16; ++r) oacc[dt][r] *= alpha;
-      }
-      const float moff = -mref;   // finite: the first step of a list always holds a valid key
-      float rs = 0.f;
-#pragma unroll
-      for (int t = 0; t < C::KT; ++t) {
-        float p[16];
-#pragma unroll
-        for (int r = 0; r < 16; ++r) {
-          p[r] = __builtin_amdgcn_exp2f(fmaf(sacc[t][r], cs, moff));
-          rs += p[r];
+            for (int r = 0; r < 16; ++r) oacc[dt][r] *= alpha;
         }
+      }
+      float rs = 0.f;
+      if (!__any(mref != 0.f)) {
 #pragma unroll
-        for (int u = 0; u < 2; ++u) {
-          u32x4 w;
-          w.x = pack_bf16x2(p[8 * u + 0], p[8 * u + 1]);
-          w.y = pack_bf16x2(p[8 * u + 2], p[8 * u + 3]);
-          w.z = pack_bf16x2(p[8 * u + 4], p[8 * u + 5]);
-          w.w = pack_bf16x2(p[8 * u + 6], p[8 * u + 7]);
-          pb[2 * t + u] = w;
+        for (int t = 0; t < C::KT; ++t) {
+          float p[16];
+#pragma unroll
+          for (int r = 0; r < 16; ++r) {
+            p[r] = __builtin_amdgcn_exp2f(sacc[t][r] * cs);
+            rs += p[r];
+          }
+#pragma unroll
+          for (int u = 0; u < 2; ++u) {
+            u32x4 w;
+            w.x = pack_bf16x2(p[8 * u + 0], p[8 * u + 1]);
+            w.y = pack_bf16x2(p[8 * u + 2], p[8 * u + 3]);
+            w.z = pack_bf16x2(p[8 * u + 4], p[8 * u + 5]);
+            w.w = pack_bf16x2(p[8 * u + 6], p[8 * u + 7]);
+            pb[2 * t + u] = w;
+          }
+        }
+      } else {
+#pragma unroll
+        for (int t = 0; t < C::KT; ++t) {
+          float p[16];
+#pragma unroll
+          for (int r = 0; r < 16; ++r) {
+            p[r] = __builtin_amdgcn_exp2f(fmaf(sacc[t][r], cs, -mref));
+            rs += p[r];
+          }
+#pragma unroll
+          for (int u = 0; u < 2; ++u) {
+            u32x4 w;
+            w.x = pack_bf16x2(p[8 * u + 0], p[8 * u + 1]);
+            w.y = pack_bf16x2(p[8 * u + 2], p[8 * u + 3]);
+            w.z = pack_bf16x2(p[8 * u + 4], p[8 * u + 5]);
+            w.w = pack_bf16x2(p[8 * u + 6], p[8 * u + 7]);
+            pb[2 * t + u] = w;
+          }
         }
       }
       lpart += rs;
@@ -684,10 +728,11 @@ __global__ __launch_bounds__(512, 1) void attn_kernel(Dims dm, AttnArgs a, Sched
     }
     // tile s+1 has landed (this wave's share; the barrier that follows covers the group), and so
     // have the query rows of the next item
+    // (loads return in order: only this phase's own requests may still be out)
     if constexpr (first_of_item) {
-      if (!have_output) __builtin_amdgcn_s_waitcnt(0x0F70);
+      if (!have_output) wait_loads_leaving<VLOADS>();
     } else {
-      __builtin_amdgcn_s_waitcnt(0x0F70);          // vmcnt(0)
+      wait_loads_leaving<VLOADS>();
     }
   };
 

@@ -40,7 +40,15 @@ def test_block_counts_and_workspace(lib):
     assert (n, m, w) == (929, 931, 30)
     pool_ws, attn_ws = rb.rsa_workspace_bytes(_shape())
     assert pool_ws > 0 and pool_ws % 256 == 0
-    assert attn_ws == 1 * 2 * 8 * 128 * 4 + 256        # C_n, then the launch order (2 * 8 int32, padded to 256 B)
+    # C_n (fp32 [b][h][N][d]), the row order (one int32 per query block, padded to 256 B), then the
+    # schedule of the persistent kernel: a table with room for every query block, two counters per queue
+    comp, order = 1 * 2 * 8 * 128 * 4, 256
+    assert attn_ws % 256 == 0 and attn_ws >= comp + order + 2 * 8 * 4 + 2 * 256
+    # the headline shape fits the scratch array of the entry point that allocates nothing
+    big = 118800 + 256
+    _, attn_big = rb.rsa_workspace_bytes(_shape(t_video=118800, t_text=256, heads=24, stride_b=24 * big * 128,
+                                                stride_h=big * 128))
+    assert attn_big <= rb.RSA_STATIC_SCRATCH_BYTES
 
 
 @pytest.mark.parametrize("kw,code", [
