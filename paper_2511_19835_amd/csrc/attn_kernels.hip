@@ -109,6 +109,16 @@ __device__ __forceinline__ float half_wave_sum(float v) {
   return lo + hi;
 }
 
+// The lane number, worked out where it is asked for. What happens once per item (query rows, epilogue)
+// takes its lane-dependent addresses from this: values derived from the lane number at the top of the
+// kernel would be live across the whole step loop, where there is no register left for them, and a
+// spilled vector register comes back with a wait for every load in flight, tile requests included.
+__device__ __forceinline__ int lane_now() {
+  int l;
+  asm volatile("v_mbcnt_lo_u32_b32 %0, -1, 0\n\tv_mbcnt_hi_u32_b32 %0, -1, %0" : "=v"(l));
+  return l;
+}
+
 // The running softmax reference only moves when a score is more than this many binades away from it
 // (above it; in the first step of an item, either way): probabilities then stay within 2^+-kLazyBits of
 // one another's scale, far inside what fp32 sums and bf16 operands hold, and the accumulators are
@@ -224,15 +234,24 @@ __global__ __launch_bounds__(512, 1) void attn_kernel(Dims dm, AttnArgs a, Sched
     int has_list;
     const_list_t list;      // its list of key blocks; a dense row: any readable address
     uint64_t Kbytes, Vtbytes;   // K rows and V^T tiles of its (batch, head)
+    int64_t qo_off;         // element offset of its first query row in Q and in O
+    int q_t0, q_count;      // its first token and how many it has
   };
-  auto load_item = [&](int k) __attribute__((always_inline)) {
+  // An item from its record and the raw count of its list (raw_count: one scalar load, nothing else, so
+  // that the load can be requested well ahead of make_item).
+  auto raw_count = [&](int rec) __attribute__((always_inline)) {
+    typedef const int32_t __attribute__((address_space(4))) * const_i32_t;
+    const int bh = rec / RSA_MAX_BLOCKS, qb = rec % RSA_MAX_BLOCKS;
+    const bool sp = !dense_all && qb < dm.n;
+    return sp ? ((const_i32_t)(uintptr_t)a.count)[(size_t)bh * dm.n + qb] : dm.m;
+  };
+  auto make_item = [&](int rec, int cnt) __attribute__((always_inline)) {
     Item it;
-    const int rec = my_record(k);
     it.bh = rec / RSA_MAX_BLOCKS;
     it.qb = rec % RSA_MAX_BLOCKS;
     const bool sp = !dense_all && it.qb < dm.n;
     const size_t vrow = (size_t)it.bh * dm.n + it.qb;
-    it.nlist = sp ? list_length(a, dm, vrow) : dm.m;
+    it.nlist = min(max(cnt, 1), dm.m);        // as list_length() holds it
     it.ns = it.nlist * C::SPB;
     it.has_list = sp ? 1 : 0;
     const int b = it.bh / dm.heads, h = it.bh % dm.heads;
@@ -241,7 +260,15 @@ __global__ __launch_bounds__(512, 1) void attn_kernel(Dims dm, AttnArgs a, Sched
     it.list = (const_list_t)(uintptr_t)(sp ? (const void*)(a.block_idx + vrow * dm.m) : (const void*)a.Q);
     it.Kbytes = (uint64_t)(uintptr_t)(a.K + base);
     it.Vtbytes = (uint64_t)(uintptr_t)(a.Vt + (size_t)it.bh * dm.m * D * BLK);
+    const int64_t t0 = dm.block_start(it.qb);
+    it.q_t0 = (int)t0;
+    it.q_count = dm.block_count(it.qb);
+    it.qo_off = base + t0 * dm.st;
     return it;
+  };
+  auto load_item = [&](int k) __attribute__((always_inline)) {
+    const int rec = my_record(k);
+    return make_item(rec, raw_count(rec));
   };
 
   // ---- direct-to-LDS loads ---------------------------------------------------------------
@@ -360,23 +387,23 @@ __global__ __launch_bounds__(512, 1) void attn_kernel(Dims dm, AttnArgs a, Sched
   // ---- the item being computed, the one after it, and the one whose output is still to be written
   Item cur = {}, nxt = {};
   int nxt_valid = 0, k_next = 0;       // k_next: the first item not yet loaded
+  int rec_ahead = 0;                   // ... and its record, read an item ahead
   // what the epilogue needs of the item that has just ended
-  int done_bh = 0, done_qb = 0, done_sparse = 0;
+  int done_bh = 0, done_sparse = 0, done_q_t0 = 0, done_q_count = 0;
+  int64_t done_qo_off = 0;
 
   // Q as the B operand of S^T = K Q^T, resident in registers; the next item's rows replace it right
   // behind the last K Q^T of the current one.
   bf16x8 qreg[C::KS];
   const float cs = dm.scale * kLog2e;   // scores -> binades
   auto load_q = [&](const Item& it) __attribute__((always_inline)) {
-    const int b = it.bh / dm.heads, h = it.bh % dm.heads;
-    const uint16_t* Qb = a.Q + (int64_t)b * dm.sb + (int64_t)h * dm.sh;
-    const int q_count = dm.block_count(it.qb);
-    const int64_t q_t0 = dm.block_start(it.qb);
-    const int q = wave * 32 + l32;
+    const int ln = lane_now();
+    const int q = wave * 32 + ln % 32;
+    const uint16_t* qrow = a.Q + it.qo_off + (int64_t)q * dm.st + 8 * (ln / 32);
 #pragma unroll
     for (int s = 0; s < C::KS; ++s) {
       uint4 v = make_uint4(0, 0, 0, 0);
-      if (q < q_count) v = *reinterpret_cast<const uint4*>(Qb + (q_t0 + q) * dm.st + 16 * s + 8 * hf);
+      if (q < it.q_count) v = *reinterpret_cast<const uint4*>(qrow + 16 * s);
       qreg[s] = __builtin_bit_cast(bf16x8, v);
     }
   };
@@ -388,42 +415,74 @@ __global__ __launch_bounds__(512, 1) void attn_kernel(Dims dm, AttnArgs a, Sched
   float mref = 0.f, lpart = 0.f;         // softmax reference (log2 domain) and this lane's partial row sum
 
   // Epilogue of one item: O = R_n * acc / l + C_n (video rows; text rows: acc / l), bf16; then the
-  // running state starts over for the next item.
+  // running state starts over for the next item. R_n and C_n are requested a step ahead (in the
+  // softmax phase of the item's last step): lane j holds elements CV*j .. CV*j+CV-1 of C_n, and every
+  // lane collects the 64 it needs through the LDS crossbar -- no memory latency is left in here.
+  constexpr int CV = D / 64;
+  float done_comp[CV];
+#pragma unroll
+  for (int j = 0; j < CV; ++j) done_comp[j] = 0.f;
+  float done_rfac = 1.0f;
+  auto request_epilogue = [&](const Item& it) __attribute__((always_inline)) {
+    const size_t vrow = (size_t)it.bh * dm.n + it.qb;          // row of the per-video-block tensors
+    done_rfac = 1.0f;
+    if (it.has_list && (a.flags & RSA_RECTIFY_CRITICAL)) {
+      typedef const float __attribute__((address_space(4))) * const_f32_t;    // scalar load
+      done_rfac = ((const_f32_t)(uintptr_t)a.R)[vrow];
+    }
+    if (it.has_list && (a.flags & RSA_COMPENSATE)) {
+      const float* crow = a.comp + vrow * D + lane_now() * CV;
+#pragma unroll
+      for (int j = 0; j < CV; ++j) done_comp[j] = crow[j];
+    }
+  };
+  auto settle_item_loads = [&]() __attribute__((always_inline)) {       // a use of everything load_q and request_epilogue asked for
+#pragma unroll
+    for (int ks = 0; ks < C::KS; ++ks) asm volatile("" : "+v"(qreg[ks]));
+#pragma unroll
+    for (int j = 0; j < CV; ++j) asm volatile("" : "+v"(done_comp[j]));
+  };
   auto write_output = [&]() __attribute__((always_inline)) {
-    const int b = done_bh / dm.heads, h = done_bh % dm.heads;
-    const size_t vrow = (size_t)done_bh * dm.n + done_qb;      // row of the per-video-block tensors
     const bool do_comp = done_sparse && (a.flags & RSA_COMPENSATE);
-    const float rfac = (done_sparse && (a.flags & RSA_RECTIFY_CRITICAL)) ? a.R[vrow] : 1.0f;
-    uint16_t* Ob = a.O + (int64_t)b * dm.sb + (int64_t)h * dm.sh;
-    const int q_count = dm.block_count(done_qb);
-    const int64_t q_t0 = dm.block_start(done_qb);
+    const int q_count = done_q_count;
     const float lsum = half_wave_sum(lpart);
-    const int q = wave * 32 + l32;
-    if (q < q_count) {
-      const float f = rfac / lsum;
-      uint16_t* orow = Ob + (q_t0 + q) * dm.st;
-      const float* crow = a.comp + vrow * D;     // C_n of this query block (only read when do_comp)
+    const int ln = lane_now();
+    const int hf = ln / 32;                        // (a copy of its own: see lane_now)
+    const int q = wave * 32 + ln % 32;
+    const float f = done_rfac / lsum;
+    uint16_t* orow = a.O + done_qo_off + (int64_t)q * dm.st;
+    const int hf_lane4 = (4 * hf / CV) * 4;        // byte address of lane (4 hf)/CV for the crossbar
 #pragma unroll
-      for (int dt = 0; dt < C::DT; ++dt)
+    for (int dt = 0; dt < C::DT; ++dt) {
+      // the 16 elements of C_n that go with this accumulator tile, all requested before the first is used
+      // (element 32 dt + 8 g + 4 hf + e; every lane takes part: one outside the block still lends its share)
+      float cadd[16];
 #pragma unroll
-        for (int g = 0; g < 4; ++g) {
-          const int d0 = 32 * dt + 8 * g + 4 * hf;
-          float o[4];
+      for (int r = 0; r < 16; ++r) cadd[r] = 0.f;
+      if (do_comp) {
 #pragma unroll
-          for (int e = 0; e < 4; ++e) o[e] = oacc[dt][4 * g + e] * f;
-          if (do_comp) {
-            const floatx4 c4 = *reinterpret_cast<const floatx4*>(crow + d0);
+        for (int r = 0; r < 16; ++r) {
+          const int dc = 32 * dt + 8 * (r / 4) + (r % 4);        // + 4 hf: a multiple of CV
+          const int c = __builtin_amdgcn_ds_bpermute(hf_lane4 + (dc / CV) * 4, __builtin_bit_cast(int, done_comp[dc % CV]));
+          cadd[r] = __builtin_bit_cast(float, c);
+        }
+      }
 #pragma unroll
-            for (int e = 0; e < 4; ++e) o[e] += c4[e];
-          }
+      for (int g = 0; g < 4; ++g) {
+        const int d0 = 32 * dt + 8 * g + 4 * hf;
+        float o[4];
+#pragma unroll
+        for (int e = 0; e < 4; ++e) o[e] = fmaf(oacc[dt][4 * g + e], f, cadd[4 * g + e]);
+        if (q < q_count) {
           uint2 w;
           w.x = pack_bf16x2(o[0], o[1]);
           w.y = pack_bf16x2(o[2], o[3]);
           *reinterpret_cast<uint2*>(orow + d0) = w;
         }
-      if (a.lse && hf == 0)
-        a.lse[((size_t)done_bh * dm.t) + q_t0 + q] = (mref + log2f(lsum)) * 0.6931471805599453f;
+      }
     }
+    if (q < q_count && a.lse && hf == 0)
+      a.lse[((size_t)done_bh * dm.t) + done_q_t0 + q] = (mref + log2f(lsum)) * 0.6931471805599453f;
 #pragma unroll
     for (int dt = 0; dt < C::DT; ++dt)
 #pragma unroll
@@ -449,7 +508,7 @@ __global__ __launch_bounds__(512, 1) void attn_kernel(Dims dm, AttnArgs a, Sched
   // it was filled: by then every wave of the group has passed the barrier that follows its last
   // read. Every item has an even number of steps (SPB = 2 per key block), so the position inside a
   // key block and the K stage both follow from the parity of s, which the unrolled loop knows.
-  int m_nxt = 0;          // key block that the next new-block step opens
+  int m_nxt_e = 0, m_nxt_j = 0;   // key block that the next new-block step opens: entry m_nxt_e of a list, or block m_nxt_j (>= 0) of a dense row
   int kvc_cur = BLK;      // valid keys in the block of the current step
   int kvc_nxt = BLK;
   auto group_barrier = [&]() __attribute__((always_inline)) {
@@ -551,7 +610,7 @@ __global__ __launch_bounds__(512, 1) void attn_kernel(Dims dm, AttnArgs a, Sched
         if constexpr (i == 0) {
           if constexpr (PART_NEXT == 0) {
             const bool in_next = last_of_item && nxt_valid;
-            open_block(m_nxt, in_next ? nxt.Kbytes : cur.Kbytes, in_next ? nxt.Vtbytes : cur.Vtbytes);
+            open_block(m_nxt_j >= 0 ? m_nxt_j : m_nxt_e, in_next ? nxt.Kbytes : cur.Kbytes, in_next ? nxt.Vtbytes : cur.Vtbytes);
           }
           kvc_nxt = blk_count;
         } else {
@@ -591,6 +650,36 @@ __global__ __launch_bounds__(512, 1) void attn_kernel(Dims dm, AttnArgs a, Sched
     constexpr int FETCH = decltype(fetchc)::value;
     __builtin_amdgcn_s_setprio(0);
     constexpr int VLOADS = SPLIT_LOADS ? C::VPW : 0;  // requests of this phase: the V^T rows of step s+1
+    // The last step of an item: what the switch to the next item and the epilogue need from memory is
+    // requested here, a whole softmax ahead of its use -- R_n and C_n of this item, the list length of
+    // the item after the next (its record came in an item ago), the record of the one after that.
+    int cnt_ahead = 0, rec_new = 0;
+    bool more = false;
+    if constexpr (last_of_item) {
+      request_epilogue(cur);
+      more = k_next < n_my_items;
+      if (more) cnt_ahead = raw_count(rec_ahead);
+      if (k_next + 1 < n_my_items) rec_new = my_record(k_next + 1);
+    }
+    // The list entry of step s+2 (an even step opens a key block) for M(s+1): requested ahead of the
+    // softmax, which hides the scalar cache miss that every sixteenth entry (and the head of every list)
+    // is. Only the load is here -- what the entry means (a dense row has none: its j-th block is j)
+    // is settled where M(s+1) opens the block.
+    if constexpr (FETCH == 1) {
+      m_nxt_e = cur.list[cur.has_list ? fj : 0];
+      m_nxt_j = cur.has_list ? -1 : fj;
+      fj += 1;
+    } else if constexpr (FETCH == 2) {
+      // it may be the first entry of the next item; past the last item, the last entry again (a valid
+      // block: the tile requested for a step that does not exist is never read)
+      const bool own = fj < cur.nlist, follow = !own && nxt_valid;
+      const_list_t lp = follow ? nxt.list : cur.list;
+      const int hl = follow ? nxt.has_list : cur.has_list;
+      const int j = own ? fj : (follow ? 0 : cur.nlist - 1);
+      m_nxt_e = lp[hl ? j : 0];
+      m_nxt_j = hl ? -1 : j;
+      fj += 1;
+    }
     if constexpr (SPLIT_LOADS && !first_of_item) {
       static_for<0, C::VPW>([&](auto ic) __attribute__((always_inline)) { issue_load(vt_next, IntC<C::KPW + decltype(ic)::value>{}); });
     }
@@ -688,18 +777,6 @@ __global__ __launch_bounds__(512, 1) void attn_kernel(Dims dm, AttnArgs a, Sched
       }
       lpart += rs;
     }
-    // The list entry of step s+2 (an even step opens a key block) for M(s+1): fetched a phase ahead.
-    if constexpr (FETCH == 1) {
-      m_nxt = list_entry(cur, fj);
-      fj += 1;
-    } else if constexpr (FETCH == 2) {
-      // it may be the first entry of the next item; past the last item, the last entry again (a valid
-      // block: the tile requested for a step that does not exist is never read)
-      if (fj < cur.nlist) m_nxt = list_entry(cur, fj);
-      else if (nxt_valid) m_nxt = list_entry(nxt, 0);
-      else m_nxt = list_entry(cur, cur.nlist - 1);
-      fj += 1;
-    }
     kvc_cur = kvc_nxt;
     // the probabilities are complete here: nothing of the softmax may sink behind the barrier
     // into the MFMA phase, where it would take the other group's VALU time
@@ -715,14 +792,17 @@ __global__ __launch_bounds__(512, 1) void attn_kernel(Dims dm, AttnArgs a, Sched
     if constexpr (last_of_item) {
       // the item has ended: its output waits for the last P V product; the next item takes its place
       done_bh = cur.bh;
-      done_qb = cur.qb;
       done_sparse = cur.has_list;
+      done_q_t0 = cur.q_t0;
+      done_q_count = cur.q_count;
+      done_qo_off = cur.qo_off;
       have_output = 1;
       if (nxt_valid) {
         cur = nxt;
         fj = 1;                          // entry 0 was fetched two steps ago
-        nxt_valid = k_next < n_my_items;
-        if (nxt_valid) nxt = load_item(k_next);
+        nxt_valid = more;
+        if (more) nxt = make_item(rec_ahead, cnt_ahead);
+        rec_ahead = rec_new;
         k_next += 1;
       }
     }
@@ -734,6 +814,12 @@ __global__ __launch_bounds__(512, 1) void attn_kernel(Dims dm, AttnArgs a, Sched
     } else {
       wait_loads_leaving<VLOADS>();
     }
+    if constexpr (last_of_item) {
+      // The compiler waits for the loads it knows of (the query rows, C_n) where they are first used, and
+      // such a wait covers the tile requests as well: it belongs here, where the youngest request is a
+      // whole phase old, not behind the first requests of the next MFMA phase.
+      settle_item_loads();
+    }
   };
 
   const bool active = n_my_items > 0;
@@ -742,6 +828,7 @@ __global__ __launch_bounds__(512, 1) void attn_kernel(Dims dm, AttnArgs a, Sched
     nxt_valid = n_my_items > 1;
     if (nxt_valid) nxt = load_item(1);
     k_next = 2;
+    if (n_my_items > 2) rec_ahead = my_record(2);
     load_q(cur);
     // Q must have arrived before the first direct-to-LDS load is requested: the compiler
     // does not see those loads, and would otherwise place its own wait for Q -- a wait for
