@@ -8,6 +8,8 @@
 // integer work (ties: lower block index first). The optional weight threshold p extends
 // the kept prefix, in the same descending order, until the kept A^pool exceeds p.
 // Outputs: mask bits, ascending block list, count, and R_n = sum of kept A^pool.
+#include <type_traits>
+
 #include "rsa_common.hpp"
 
 namespace rsa {
@@ -20,9 +22,25 @@ __device__ inline uint32_t orderable_key(float x) {
 __device__ inline int lanes_below(unsigned long long mask) {
   return __builtin_amdgcn_mbcnt_hi((uint32_t)(mask >> 32), __builtin_amdgcn_mbcnt_lo((uint32_t)mask, 0));
 }
+// Sum over the 64 lanes with data-parallel-primitive moves (row shifts inside the rows of 16 lanes, then
+// the two row broadcasts); every lane gets the total.
 __device__ inline float wave_sum(float v) {
+  auto step = [&](auto ctrl, auto row_mask) __attribute__((always_inline)) {
+    const int o = __builtin_amdgcn_update_dpp(0, __builtin_bit_cast(int, v), decltype(ctrl)::value,
+                                              decltype(row_mask)::value, 0xf, false);
+    v += __builtin_bit_cast(float, o);
+  };
+  step(std::integral_constant<int, 0x111>{}, std::integral_constant<int, 0xf>{});   // row_shr:1
+  step(std::integral_constant<int, 0x112>{}, std::integral_constant<int, 0xf>{});   // row_shr:2
+  step(std::integral_constant<int, 0x114>{}, std::integral_constant<int, 0xf>{});   // row_shr:4
+  step(std::integral_constant<int, 0x118>{}, std::integral_constant<int, 0xf>{});   // row_shr:8
+  step(std::integral_constant<int, 0x142>{}, std::integral_constant<int, 0xa>{});   // row_bcast:15 into rows 1 and 3
+  step(std::integral_constant<int, 0x143>{}, std::integral_constant<int, 0xc>{});   // row_bcast:31 into rows 2 and 3
+  return __builtin_bit_cast(float, __builtin_amdgcn_readlane(__builtin_bit_cast(int, v), 63));
+}
+__device__ inline uint32_t wave_max_u32(uint32_t v) {
 #pragma unroll
-  for (int o = 32; o > 0; o >>= 1) v += __shfl_xor(v, o);
+  for (int o = 32; o > 0; o >>= 1) v = max(v, (uint32_t)__shfl_xor((int)v, o));
   return v;
 }
 __device__ inline float wave_inclusive_scan(float v, int lane) {
@@ -58,13 +76,31 @@ __global__ __launch_bounds__(256) void select_kernel(Dims dm, SelectArgs a) {
     rv[s] = (m < M) ? A[m] : 0.f;
   }
 
-  // k-th largest key
-  uint32_t tau = 0;
-  for (int bit = 31; bit >= 0; --bit) {
+  // k-th largest key. The bits that all keys of the row share need no search (a candidate with such a
+  // bit set is below or at every key, one with it clear above every key), and the search ends as soon as
+  // a candidate is matched or passed by exactly `keep` keys: those are the kept blocks, whatever the
+  // lower bits of the k-th key.
+  uint32_t kmax = 0, nkmin = 0;
+#pragma unroll
+  for (int s = 0; s < slots; ++s) {
+    const bool valid = s * 64 + lane < M;
+    kmax = max(kmax, key_at(s));
+    nkmin = max(nkmin, valid ? ~key_at(s) : 0u);
+  }
+  kmax = wave_max_u32(kmax);
+  const uint32_t kmin = ~wave_max_u32(nkmin);
+  const int vary = 32 - __builtin_clz((kmax ^ kmin) | 1u);      // low bits in which keys of this row differ (at least 1)
+  uint32_t tau = vary >= 32 ? 0u : (kmax >> vary) << vary;
+  bool exact = false;
+  for (int bit = vary - 1; bit >= 0 && !exact; --bit) {
     const uint32_t cand = tau | (1u << bit);
     int cnt = 0;
     _Pragma("unroll") for (int s = 0; s < slots; ++s) cnt += __popcll(__ballot(key_at(s) >= cand));
     if (cnt >= a.keep) tau = cand;
+    if (cnt == a.keep) {
+      tau = cand - 1;             // "key > tau" is "key >= cand"; no key equal to tau is kept
+      exact = true;
+    }
   }
   int n_gt = 0;
   _Pragma("unroll") for (int s = 0; s < slots; ++s) n_gt += __popcll(__ballot(key_at(s) > tau));
