@@ -271,6 +271,39 @@ def main():
                             "achieved": pv_bytes / (pv_ms * 1e-3) / 1e9, "peak": PEAK_HBM_GBS, "unit": "GB/s",
                             "frac": pv_bytes / (pv_ms * 1e-3) / 1e9 / PEAK_HBM_GBS, "bytes": pv_bytes, "ms": pv_ms}
 
+    # the implicit attention alone (rsa_implicit_attention = text_mass_kernel + ipar_fused_kernel): writes the three
+    # N x M tensors once, reads the pooled vectors and the text keys
+    e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+    rb.rsa_implicit_attention(buf.shape, K, buf.Qp, buf.Kp, buf.Spool, buf.Lmass, buf.Apool)
+    torch.cuda.synchronize()
+    e0.record()
+    for _ in range(5):
+        rb.rsa_implicit_attention(buf.shape, K, buf.Qp, buf.Kp, buf.Spool, buf.Lmass, buf.Apool)
+    e1.record()
+    torch.cuda.synchronize()
+    ia_ms = e0.elapsed_time(e1) / 5
+    ia_bytes = 3.0 * H * N * M * 4 + (N + M) * H * d * 4 + H * cfg.t_text * d * 2
+    ia_flop = 2.0 * H * N * (M + cfg.t_text) * d          # fp32 matrix work of the pooled scores (+ VALU text scores)
+    out["roofline_scores"] = {"kernel": "text_mass_kernel + ipar_fused_kernel (rsa_implicit_attention)", "bound": "hbm",
+                              "achieved": ia_bytes / (ia_ms * 1e-3) / 1e9, "peak": PEAK_HBM_GBS, "unit": "GB/s",
+                              "frac": ia_bytes / (ia_ms * 1e-3) / 1e9 / PEAK_HBM_GBS, "bytes": ia_bytes, "ms": ia_ms,
+                              "fp32_mfma_floor_ms": ia_flop / 157.3e12 * 1e3}
+    # the selection (rsa_select_blocks = select_kernel): reads Lmass and Apool once, writes the kept lists
+    e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+    e0.record()
+    for _ in range(5):
+        rb.rsa_select_blocks(buf.shape, buf.Lmass, buf.Apool, sparsity, p_thr, forced, buf.mask_bits, buf.block_idx,
+                             buf.count, buf.R)
+    e1.record()
+    torch.cuda.synchronize()
+    sel_ms = e0.elapsed_time(e1) / 5
+    sel_bytes = 2.0 * H * N * M * 4 + float(counts.sum()) * 4 + H * N * (buf.mask_bits.shape[-1] * 4 + 8)
+    if forced is not None:
+        sel_bytes += H * N * buf.mask_bits.shape[-1] * 4
+    out["roofline_select"] = {"kernel": "select_kernel (rsa_select_blocks)", "bound": "hbm",
+                              "achieved": sel_bytes / (sel_ms * 1e-3) / 1e9, "peak": PEAK_HBM_GBS, "unit": "GB/s",
+                              "frac": sel_bytes / (sel_ms * 1e-3) / 1e9 / PEAK_HBM_GBS, "bytes": sel_bytes, "ms": sel_ms}
+
     # token reordering around the layer (not part of a step: inputs of a step are already in tile order)
     if cfg.grid is not None:
         tile = synth.default_tile(cfg.block)

@@ -122,6 +122,16 @@ int rsa_pool(const rsa_shape* shape, const void* Q, const void* K, const void* V
 int rsa_pool_values(const rsa_shape* shape, const void* V, float* Vp, void* Vt, void* stream);
 
 /*
+ * Alg. 1 steps 5-7 alone (Sec. 3.2, Sec. 4.1): the implicit full attention from pooled vectors that
+ * an earlier rsa_pool call left in Qp and Kp, together with the text keys of K -- Spool, Lmass and
+ * Apool exactly as rsa_pool writes them, nothing else. For callers that re-derive A^pool from stored
+ * pooled vectors, and the unit this stage is timed in. Same layouts and ownership as in rsa_pool; the
+ * three outputs are fully overwritten.
+ */
+int rsa_implicit_attention(const rsa_shape* shape, const void* K, const float* Qp, const float* Kp,
+                           float* Spool, float* Lmass, float* Apool, void* stream);
+
+/*
  * Alg. 1 steps 13-14 and 19, per video query block n:
  *   keep the k = clamp(M - floor(sparsity*M + 1e-6), 1, M) blocks of largest Lmass (equal
  *   keys: lower block index first); if p > 0 extend, in the same descending order, until

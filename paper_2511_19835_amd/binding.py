@@ -24,7 +24,7 @@ RSA_MAX_BLOCKS = 4096
 RSA_STATIC_SCRATCH_BYTES = 16 << 20
 
 EXPORTS = (
-    "rsa_block_counts", "rsa_workspace_bytes", "rsa_pool", "rsa_pool_values", "rsa_adjacency_mask", "rsa_reorder_tokens", "rsa_select_blocks",
+    "rsa_block_counts", "rsa_workspace_bytes", "rsa_pool", "rsa_pool_values", "rsa_implicit_attention", "rsa_adjacency_mask", "rsa_reorder_tokens", "rsa_select_blocks",
     "rsa_sparse_attn_rectified", "rsa_sparse_attn_rectified_static", "rsa_status_string",
 )
 
@@ -68,6 +68,8 @@ def _lib() -> ctypes.CDLL:
         lib.rsa_pool.restype = ctypes.c_int
         lib.rsa_pool_values.argtypes = [shp, vp, vp, vp, vp]
         lib.rsa_pool_values.restype = ctypes.c_int
+        lib.rsa_implicit_attention.argtypes = [shp] + [vp] * 7
+        lib.rsa_implicit_attention.restype = ctypes.c_int
         lib.rsa_select_blocks.argtypes = [shp, vp, vp, ctypes.c_double, ctypes.c_double, vp, vp, vp, vp, vp, vp]
         lib.rsa_select_blocks.restype = ctypes.c_int
         lib.rsa_sparse_attn_rectified.argtypes = [shp] + [vp] * 10 + [ctypes.c_int, vp, vp, vp, ctypes.c_size_t, vp]
@@ -132,6 +134,11 @@ def rsa_pool(shape, Q, K, V, Qp, Kp, Vp, Vt, Spool, Apool, Lmass, Mc_bits, gapr_
                            _ptr(Spool), _ptr(Apool), _ptr(Lmass), _ptr(Mc_bits), int(gapr_mode),
                            _ptr(ws), ws.numel() * ws.element_size() if ws is not None else 0,
                            _stream_ptr(stream)), "rsa_pool")
+
+
+def rsa_implicit_attention(shape, K, Qp, Kp, Spool, Lmass, Apool, stream=None):
+    _check(_lib().rsa_implicit_attention(ctypes.byref(shape), _ptr(K), _ptr(Qp), _ptr(Kp), _ptr(Spool), _ptr(Lmass),
+                                         _ptr(Apool), _stream_ptr(stream)), "rsa_implicit_attention")
 
 
 def rsa_pool_values(shape, V, Vp, Vt, stream=None):

@@ -710,21 +710,49 @@ __global__ __launch_bounds__(512, 1) void attn_kernel(Dims dm, AttnArgs a, Sched
           }
       }
       // ---- online softmax, one query column per lane ---------------------------------
-      // Scores are counted in binades (score * scale * log2 e). The reference stays 0 -- the
-      // probabilities are then exp2 of the scaled score itself -- unless the first step of an item
-      // sees a score more than kLazyBits binades away from 0, or a later step one that far above the
-      // reference: fp32 sums and bf16 operands span 2^+-126, so nothing overflows or vanishes inside
-      // that window, and weights that far below the row maximum do not matter to any digit kept.
-      float mx = -INFINITY;
+      // Scores are counted in binades (score * scale * log2 e) from a reference that starts at 0 for
+      // every item and moves rarely: fp32 sums and bf16 operands span 2^+-126, so probabilities may
+      // sit anywhere within 2^+-kLazyBits of one another's scale. No maximum is taken on the way: the
+      // probabilities of the step are worked out against the current reference, and only when their
+      // sum says that one of them left the window (above it; in the first step of an item, all of
+      // them below it, too) is the step done again the long way -- the scores are still in registers
+      // -- with the row maximum as the new reference and everything gathered so far rescaled.
+      constexpr float kAbove = 1.0995116e12f, kBelow = 9.0949470e-13f;        // 2^+-kLazyBits
+      static_assert(kLazyBits == 40.0f, "kAbove and kBelow are 2^+-kLazyBits");
+      auto probabilities = [&]() __attribute__((always_inline)) {
+        float sum = 0.f;
 #pragma unroll
-      for (int t = 0; t < C::KT; ++t)
+        for (int t = 0; t < C::KT; ++t) {
+          float p[16];
 #pragma unroll
-        for (int r = 0; r < 16; ++r) mx = fmaxf(mx, sacc[t][r]);
-      mx = half_wave_max(mx) * cs;                     // the scale is positive
-      if constexpr (first_of_item) {
-        if (__any(fabsf(mx) > kLazyBits)) mref = mx;     // accumulators and row sum are empty: nothing to rescale
-      } else {
-        if (__any(mx > mref + kLazyBits)) {
+          for (int r = 0; r < 16; ++r) p[r] = __builtin_amdgcn_exp2f(fmaf(sacc[t][r], cs, -mref));
+#pragma unroll
+          for (int u = 0; u < 2; ++u) {
+            u32x4 w;
+            w.x = pack_bf16x2(p[8 * u + 0], p[8 * u + 1]);
+            w.y = pack_bf16x2(p[8 * u + 2], p[8 * u + 3]);
+            w.z = pack_bf16x2(p[8 * u + 4], p[8 * u + 5]);
+            w.w = pack_bf16x2(p[8 * u + 6], p[8 * u + 7]);
+            pb[2 * t + u] = w;
+#pragma unroll
+            for (int i = 0; i < 8; ++i) sum += p[8 * u + i];
+          }
+        }
+        return sum;
+      };
+      float rs = probabilities();
+      bool outside = rs > kAbove;
+      if constexpr (first_of_item) outside = outside || rs < kBelow;
+      if (__any(outside)) {
+        float mx = -INFINITY;
+#pragma unroll
+        for (int t = 0; t < C::KT; ++t)
+#pragma unroll
+          for (int r = 0; r < 16; ++r) mx = fmaxf(mx, sacc[t][r]);
+        mx = half_wave_max(mx) * cs;                   // the scale is positive
+        if constexpr (first_of_item) {
+          mref = mx;                                   // accumulators and row sum are empty: nothing to rescale
+        } else {
           const float mnew = fmaxf(mref, mx);
           const float alpha = __builtin_amdgcn_exp2f(mref - mnew);
           mref = mnew;
@@ -734,46 +762,7 @@ __global__ __launch_bounds__(512, 1) void attn_kernel(Dims dm, AttnArgs a, Sched
 #pragma unroll
             for (int r = 0; r < 16; ++r) oacc[dt][r] *= alpha;
         }
-      }
-      float rs = 0.f;
-      if (!__any(mref != 0.f)) {
-#pragma unroll
-        for (int t = 0; t < C::KT; ++t) {
-          float p[16];
-#pragma unroll
-          for (int r = 0; r < 16; ++r) {
-            p[r] = __builtin_amdgcn_exp2f(sacc[t][r] * cs);
-            rs += p[r];
-          }
-#pragma unroll
-          for (int u = 0; u < 2; ++u) {
-            u32x4 w;
-            w.x = pack_bf16x2(p[8 * u + 0], p[8 * u + 1]);
-            w.y = pack_bf16x2(p[8 * u + 2], p[8 * u + 3]);
-            w.z = pack_bf16x2(p[8 * u + 4], p[8 * u + 5]);
-            w.w = pack_bf16x2(p[8 * u + 6], p[8 * u + 7]);
-            pb[2 * t + u] = w;
-          }
-        }
-      } else {
-#pragma unroll
-        for (int t = 0; t < C::KT; ++t) {
-          float p[16];
-#pragma unroll
-          for (int r = 0; r < 16; ++r) {
-            p[r] = __builtin_amdgcn_exp2f(fmaf(sacc[t][r], cs, -mref));
-            rs += p[r];
-          }
-#pragma unroll
-          for (int u = 0; u < 2; ++u) {
-            u32x4 w;
-            w.x = pack_bf16x2(p[8 * u + 0], p[8 * u + 1]);
-            w.y = pack_bf16x2(p[8 * u + 2], p[8 * u + 3]);
-            w.z = pack_bf16x2(p[8 * u + 4], p[8 * u + 5]);
-            w.w = pack_bf16x2(p[8 * u + 6], p[8 * u + 7]);
-            pb[2 * t + u] = w;
-          }
-        }
+        rs = probabilities();
       }
       lpart += rs;
     }

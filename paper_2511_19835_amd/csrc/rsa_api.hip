@@ -230,6 +230,19 @@ int rsa_pool_values(const rsa_shape* shape, const void* V, float* Vp, void* Vt, 
   return RSA_OK;
 }
 
+int rsa_implicit_attention(const rsa_shape* shape, const void* K, const float* Qp, const float* Kp,
+                           float* Spool, float* Lmass, float* Apool, void* stream) {
+  Dims d;
+  int rc = make_dims(shape, &d);
+  if (rc != RSA_OK) return rc;
+  if (!K || !Qp || !Kp || !Spool || !Lmass || !Apool) return RSA_E_NULL;
+  rsa::ScoreArgs sa;
+  sa.K = (const uint16_t*)K; sa.Qp = Qp; sa.Kp = Kp;
+  sa.Spool = Spool; sa.Apool = Apool; sa.Lmass = Lmass;
+  if (rsa::launch_scores(d, sa, (hipStream_t)stream) != hipSuccess) return RSA_E_LAUNCH;
+  return RSA_OK;
+}
+
 int rsa_select_blocks(const rsa_shape* shape, const float* Lmass, const float* Apool,
                       double sparsity, double p, const uint32_t* forced_bits,
                       uint32_t* mask_bits, int32_t* block_idx, int32_t* count, float* R,

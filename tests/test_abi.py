@@ -72,6 +72,7 @@ def test_null_and_range_arguments_are_rejected_before_launch(lib):
     assert lib.rsa_pool(ctypes.byref(sh), *args, 1, one, 16, None) == -4
     assert lib.rsa_pool(ctypes.byref(sh), *args, 1, ctypes.c_void_p(8), 1 << 30, None) == -4
     assert lib.rsa_pool_values(ctypes.byref(sh), one, None, one, None) == -1
+    assert lib.rsa_implicit_attention(ctypes.byref(sh), one, one, one, one, None, one, None) == -1
     sel = lambda sp, p, l=one: lib.rsa_select_blocks(ctypes.byref(sh), l, one, sp, p, None, one, one, one, one, None)
     assert sel(1.5, 0.0) == -5 and sel(0.5, -0.1) == -5 and sel(float("nan"), 0.0) == -5
     assert sel(0.5, 0.0, None) == -1

@@ -208,6 +208,67 @@ def test_non_default_softmax_scale(gpu):
     _run_and_compare(gpu, EDGE["ragged_d64_b128"], seed=14, scale=0.2, sparsity=0.8)
 
 
+def test_scores_far_from_the_softmax_reference(gpu):
+    """Alg. 1 steps 16-17 with scores that leave any fixed window: the lists come from a selection at the
+    default scale, the attention runs with a scale 40 times larger, so that the scaled scores of a row lie
+    hundreds of binades apart. Queries are made non-negative and the keys of block 0 (kept by every row: a
+    forced bit) non-positive, so that every score of the first block a row meets is far below 0, and later
+    blocks hold scores far above them. Whatever reference the kernel keeps for its running softmax has to
+    move off 0 at once and up later, and the output and the log-sum-exp must still be those of the exact
+    softmax over the kept keys."""
+    import torch
+    import parity
+    from oracle import rsa_oracle as ro
+    from paper_2511_19835_amd import binding as rb
+    for name, seed in (("d128_b64_text", 21), ("ragged_d64_b128", 22)):
+        cfg = EDGE[name]
+        Qb, Kb, Vb = synth.make_inputs(cfg, seed, [0])
+        Qb = Qb & np.uint16(0x7fff)
+        Kb = Kb.copy()
+        Kb[0, 0, :cfg.block] |= np.uint16(0x8000)
+        Q, K, V = (gpu.bits_to_device(x) for x in (Qb, Kb, Vb))
+        buf = rb.allocate(Q, cfg.t_video, cfg.t_text, cfg.block)
+        rb.rsa_pool(buf.shape, Q, K, V, buf.Qp, buf.Kp, buf.Vp, buf.Vt, buf.Spool, buf.Apool, buf.Lmass, buf.Mc_bits,
+                    0, buf.pool_ws)
+        forced = torch.zeros_like(buf.mask_bits)
+        forced[..., 0] = 1
+        rb.rsa_select_blocks(buf.shape, buf.Lmass, buf.Apool, 0.6, 0.0, forced, buf.mask_bits, buf.block_idx,
+                             buf.count, buf.R)
+        scale = 40.0 / np.sqrt(cfg.head_dim)
+        big = rb.make_shape(Q, cfg.t_video, cfg.t_text, cfg.block, scale)
+        O = torch.full_like(Q, float("nan"))
+        lse = torch.full((1, 1, cfg.t_total), float("nan"), dtype=torch.float32, device=Q.device)
+        rb.rsa_sparse_attn_rectified(big, Q, K, buf.Vt, buf.block_idx, buf.count, buf.mask_bits, buf.R, buf.Apool,
+                                     buf.Mc_bits, buf.Vp, 0, O, lse, buf.attn_ws)
+        torch.cuda.synchronize()
+        part = ro.partition(cfg.t_video, cfg.t_text, cfg.block)
+        mask = gpu.unpack_bits(buf.mask_bits[0, 0].cpu().numpy(), part.n_blocks)
+        assert mask[:, 0].all()
+        Qf, Kf, Vf = (ro.bf16_bits_to_f64(x[0, 0]) for x in (Qb, Kb, Vb))
+        # the spread this test is about, in binades: block 0 against the best kept key of a row
+        X = (Qf @ Kf.T) * scale * np.log2(np.e)
+        assert X[:, :cfg.block].max() < -45.0
+        kept_cols = np.repeat(mask, part.counts, axis=1)                      # [N, T]: kept keys of a query block
+        block_of_token = np.repeat(np.arange(part.n_video), part.counts[:part.n_video])
+        best = np.where(kept_cols[block_of_token], X[:cfg.t_video], -np.inf).max(axis=1)
+        assert np.median(best - X[:cfg.t_video, :cfg.block].max(axis=1)) > 45.0
+        O_ref = np.empty_like(Qf)
+        O_ref[:cfg.t_video] = ro.sparse_attention(Qf, Kf, Vf, mask, part, scale)
+        if cfg.t_text:
+            O_ref[cfg.t_video:] = ro.dense_attention(Qf[cfg.t_video:], Kf, Vf, scale)
+        O_gpu = ro.bf16_bits_to_f64(gpu.device_to_bits(O[0, 0]))
+        assert np.isfinite(O_gpu).all()
+        err = O_gpu - O_ref
+        assert np.abs(err).max() <= parity.OUT_MAX_ABS
+        assert np.linalg.norm(err) / np.linalg.norm(O_ref) <= parity.OUT_REL_L2
+        for n in (0, part.n_video // 2, part.n_video - 1):
+            rows = part.tokens(n)
+            cols = np.nonzero(kept_cols[n])[0]
+            S = Qf[rows] @ Kf[cols].T * scale
+            want = np.log(np.exp(S - S.max(axis=1, keepdims=True)).sum(axis=1)) + S.max(axis=1)
+            np.testing.assert_allclose(lse[0, 0, rows].cpu().numpy(), want, rtol=2e-5, atol=2e-3)
+
+
 def test_attention_without_a_workspace(gpu):
     """ws = NULL is legal without RSA_COMPENSATE: the rows are then launched in index order."""
     _run_and_compare(gpu, EDGE["d128_b64_text"], seed=15, flags=1, attn_workspace=False)
@@ -564,6 +625,28 @@ def test_masks_reused_for_a_second_call(gpu):
         err = ro.bf16_bits_to_f64(out["O2_bits"][0, h]) - O_ref
         assert np.abs(err).max() <= parity.OUT_MAX_ABS
         assert np.linalg.norm(err) / np.linalg.norm(O_ref) <= parity.OUT_REL_L2
+
+
+def test_implicit_attention_alone(gpu):
+    """rsa_implicit_attention recomputes Spool, Lmass and A^pool from the pooled vectors of an earlier
+    rsa_pool call: the same values as that call wrote (both run the same kernels), on a shape with a
+    ragged last video block and text blocks, for both routes through the scores (rows within and beyond
+    the one-pass kernel's 1024 blocks are covered by test_maximum_block_count through rsa_pool)."""
+    import torch
+    from paper_2511_19835_amd import binding as rb
+    cfg = synth.CONFIGS["mid"].with_(heads=2, t_text=200)
+    Qb, Kb, Vb = synth.make_inputs(cfg, 3)
+    Q, K, V = (gpu.bits_to_device(x) for x in (Qb, Kb, Vb))
+    buf = rb.allocate(Q, cfg.t_video, cfg.t_text, cfg.block)
+    rb.rsa_pool(buf.shape, Q, K, V, buf.Qp, buf.Kp, buf.Vp, buf.Vt, buf.Spool, buf.Apool, buf.Lmass, buf.Mc_bits, 1,
+                buf.pool_ws)
+    want = [t.clone() for t in (buf.Spool, buf.Lmass, buf.Apool)]
+    for t in (buf.Spool, buf.Lmass, buf.Apool):
+        t.fill_(float("nan"))
+    rb.rsa_implicit_attention(buf.shape, K, buf.Qp, buf.Kp, buf.Spool, buf.Lmass, buf.Apool)
+    torch.cuda.synchronize()
+    for got, ref in zip((buf.Spool, buf.Lmass, buf.Apool), want):
+        assert torch.equal(got, ref)
 
 
 def test_maximum_block_count(gpu):
