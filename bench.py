@@ -114,8 +114,11 @@ def cpu_baseline(cfg, sparsity, Qb, Kb, Vb, gpu_O_bits, gpu_mask, gpu_Mc, budget
 # Fabric bytes per attn_kernel launch from rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE runs of this file
 # (counter KiB x 1024 x the scale the same counter shows for a plain copy kernel: 2.0 fetch, 1.0 write).
 # A counter run cannot be made from inside the timed process, so the figure is carried here for the
-# exact workloads it was taken on and is null for any other.
-MEASURED_TRAFFIC_BYTES = {("hunyuan", 0.9, 0, 24, 128, 128): 22.04e6 * 2.0 * 1024 + 857.2e3 * 1024}
+# exact workload it was taken on and is null for any other. Provenance: the two runs listed in
+# profiles/attn_kernel_hunyuan_pmc.md, taken with the attention kernel of this tree (persistent
+# schedule, sum-checked softmax window): FETCH_SIZE 20.12e6 KiB, WRITE_SIZE 714.3e3 KiB per launch.
+# Re-measure and update both places whenever attn_kernels.hip changes what it requests.
+MEASURED_TRAFFIC_BYTES = {("hunyuan", 0.9, 0, 24, 128, 128): 20.12e6 * 2.0 * 1024 + 714.3e3 * 1024}
 
 
 def measured_traffic(cfg, sparsity, args):
