@@ -188,11 +188,14 @@ int rsa_adjacency_mask(const rsa_shape* shape, const int32_t* grid, const int32_
  * un-rectified sparse/dense attention of every row.
  * With RSA_DENSE every list/mask/R/Apool/Mc/Vp pointer may be NULL.
  * ws / ws_bytes: device scratch of at least attn_ws_bytes, 256-byte aligned (RSA_E_WORKSPACE
- * otherwise). It receives the pooled compensation term C_n (fp32 [b][h][N][d], Alg. 1 step 21)
- * and the order in which the video query blocks are launched (rows with similar lists next to
- * each other, so that they share K/V tiles in the L2 of their XCD; the results do not depend on
- * it). Required with RSA_COMPENSATE (RSA_E_NULL); without that flag it may be NULL, and the rows
- * are then launched in index order. The caller owns it; its contents afterwards are unspecified.
+ * otherwise). It receives the pooled compensation term C_n (fp32 [b][h][N][d], Alg. 1 step 21),
+ * an order of the video query blocks (rows with similar lists next to each other, so that they
+ * share K/V tiles in the L2 of their XCD) and the schedule that deals the query blocks, in that
+ * order and balanced by the length of their lists, to the resident workgroups of the attention
+ * kernel; the results do not depend on the order or the schedule. Required with RSA_COMPENSATE
+ * (RSA_E_NULL); without that flag it may be NULL, and the query blocks are then dealt in index
+ * order. With RSA_DENSE a workspace that is too small or misaligned is ignored (index order).
+ * The caller owns it; its contents afterwards are unspecified.
  */
 int rsa_sparse_attn_rectified(const rsa_shape* shape, const void* Q, const void* K, const void* Vt,
                               const int32_t* block_idx, const int32_t* count,
@@ -203,16 +206,17 @@ int rsa_sparse_attn_rectified(const rsa_shape* shape, const void* Q, const void*
 /*
  * For callers that cannot allocate device memory or hand over a workspace: code running under HIP
  * graph capture, tight serving loops, harnesses that forbid hipMalloc. Same computation, arguments,
- * results and error codes as rsa_sparse_attn_rectified, without ws / ws_bytes: the scratch (C_n and
- * the launch order) lives in a device array of RSA_STATIC_SCRATCH_BYTES (16 MiB) that is part of the
+ * results and error codes as rsa_sparse_attn_rectified, without ws / ws_bytes: the scratch (C_n, the
+ * order of the query blocks and their schedule) lives in a device array of RSA_STATIC_SCRATCH_BYTES (16 MiB) that is part of the
  * library image, one copy per GPU, held until the process ends. The call allocates and frees nothing.
  * Its first call on a device looks up that device's copy (hipGetSymbolAddress; RSA_E_LAUNCH if that
  * fails). Shapes whose attn_ws_bytes (rsa_workspace_bytes) exceed RSA_STATIC_SCRATCH_BYTES are
  * refused with RSA_E_WORKSPACE before anything is enqueued: 4 * batch * heads * N * (head_dim + 1)
- * bytes plus padding, e.g. 11.5 MB for 24 heads of 118 800 + 256 tokens at block 128, head_dim 128.
+ * bytes plus the schedule tables and padding, e.g. 11.7 MB for 24 heads of 118 800 + 256 tokens at
+ * block 128, head_dim 128.
  * Every call on a GPU uses that GPU's one array and overwrites all of it that it reads (nothing has
  * to start at zero); two calls that overlap in time on one GPU (different streams) race on it.
- * With RSA_DENSE the scratch is not touched.
+ * With RSA_DENSE the scratch is not touched (the query blocks are dealt in index order).
  */
 int rsa_sparse_attn_rectified_static(const rsa_shape* shape, const void* Q, const void* K, const void* Vt,
                                      const int32_t* block_idx, const int32_t* count,
