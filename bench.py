@@ -12,6 +12,7 @@ stream with the inputs already resident in HBM. Default workload: the HunyuanVid
 from __future__ import annotations
 
 import argparse
+import hashlib
 import json
 import os
 import sys
@@ -117,12 +118,23 @@ def cpu_baseline(cfg, sparsity, Qb, Kb, Vb, gpu_O_bits, gpu_mask, gpu_Mc, budget
 # exact workload it was taken on and is null for any other. Provenance: the two runs listed in
 # profiles/attn_kernel_hunyuan_pmc.md, taken with the attention kernel of this tree (persistent
 # schedule, sum-checked softmax window): FETCH_SIZE 20.12e6 KiB, WRITE_SIZE 714.3e3 KiB per launch.
-# Re-measure and update both places whenever attn_kernels.hip changes what it requests.
+# The figure is reported only while csrc/attn_kernels.hip is byte for byte the source the counters were
+# taken on (hash below); after any change to it, re-measure and update figure, hash and profile together.
 MEASURED_TRAFFIC_BYTES = {("hunyuan", 0.9, 0, 24, 128, 128): 20.12e6 * 2.0 * 1024 + 714.3e3 * 1024}
+MEASURED_TRAFFIC_SOURCE = "profiles/attn_kernel_hunyuan_pmc.md"
+MEASURED_TRAFFIC_KERNEL_SHA = "4a0b8c91311c264f"      # first 16 hex digits of sha256(csrc/attn_kernels.hip) at the time of the counter runs
 
 
 def measured_traffic(cfg, sparsity, args):
+    """The carried counter figure, or None: for another workload, or once the kernel source has changed since."""
     if args.mask_rule != "topk":
+        return None
+    src = os.path.join(os.path.dirname(os.path.abspath(__file__)), "paper_2511_19835_amd", "csrc", "attn_kernels.hip")
+    try:
+        with open(src, "rb") as f:
+            if hashlib.sha256(f.read()).hexdigest()[:16] != MEASURED_TRAFFIC_KERNEL_SHA:
+                return None
+    except OSError:
         return None
     return MEASURED_TRAFFIC_BYTES.get((cfg.name, round(float(sparsity), 6), args.seed, cfg.heads, cfg.head_dim, cfg.block))
 
@@ -246,7 +258,7 @@ def main():
             "kernel": "attn_kernel (rsa_sparse_attn_rectified)", "bound": "mfma",
             "achieved": attn_tflops, "peak": PEAK_BF16_MFMA_TFLOPS, "unit": "TFLOP/s",
             "frac": attn_tflops / PEAK_BF16_MFMA_TFLOPS,
-            "traffic": measured_traffic(cfg, sparsity, args),
+            "traffic": measured_traffic(cfg, sparsity, args), "traffic_source": MEASURED_TRAFFIC_SOURCE,
             "flop_per_launch": crit_flop, "critical_tile_pairs": pairs, "ms": attn_ms,
         },
         "rsa_pool_whole_call": {
