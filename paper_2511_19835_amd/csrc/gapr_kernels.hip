@@ -15,6 +15,8 @@
 // wave then walks the pooled vectors of the other side 32 at a time against the whole centred
 // block (the MFMA A operand, read from LDS just ahead of each MFMA), so the accumulators hold
 // the deviations themselves and the epilogue is one |.|-add per element. Three waves per SIMD.
+// The key side runs first and leaves DB transposed ([M][N]) in the workspace; the query side runs second
+// and never stores DA: it decides the bits of M_c from its registers, S[n][m] and DBt[m][n].
 // Measured at the benchmark shape: 0.64 ms per side, 0.52 ms with the pooled-operand loads
 // switched off (they are 8 KB from L2 per 32 MFMAs and wave), 0.36 ms of MFMA time at the
 // clock the chip holds; a resident copy of the block in registers at two waves per SIMD: 0.65. The pooled operand is rounded to
@@ -40,11 +42,18 @@ __device__ __forceinline__ int swizzled(int r, int c) { return r * CPR + (c ^ ((
 #ifndef RSA_DEV_OCC
 #define RSA_DEV_OCC 3
 #endif
-template <int D, int BLK, int NT>
+// GATE: the launch for the query side, run second. Its deviations DA[n][.] never leave the registers:
+// with the pooled score S[n][m] and the key-side deviation DBt[m][n] of the first launch (one word each
+// per lane and iteration, asked for at the start of the iteration) the lane decides its bit of M_c, and
+// a ballot makes the mask word of the iteration.
+template <int D, int BLK, int NT, bool GATE>
 __global__ __launch_bounds__(NT, RSA_DEV_OCC) void deviation_kernel(Dims dm, const uint16_t* __restrict__ X,
                                                            const float* __restrict__ Xpool, int n_blocks_x,
                                                            const uint16_t* __restrict__ PB,
-                                                           int n_other, float* __restrict__ out) {
+                                                           int n_other, float* __restrict__ out,
+                                                           const float* __restrict__ Spool,
+                                                           const float* __restrict__ DBt,
+                                                           uint32_t* __restrict__ Mc_bits) {
   constexpr int MT = BLK / 32, KS = D / 16, CPR = D / 8;
   constexpr int NW = NT / 64;                    // waves per workgroup
   constexpr int RPP = NT / CPR;                  // rows staged per pass of the workgroup
@@ -110,6 +119,12 @@ __global__ __launch_bounds__(NT, RSA_DEV_OCC) void deviation_kernel(Dims dm, con
   };
   auto iteration = [&](const u32x4 (&bv)[KS], u32x4 (&bnext)[KS], int o0) __attribute__((always_inline)) {
     if (o0 + 32 * NW < n_other) load_vectors(bnext, o0 + 32 * NW);
+    float s_val = 0.f, db_val = 0.f;
+    if constexpr (GATE) {
+      const int m = o0 + l32 < n_other ? o0 + l32 : n_other - 1;
+      s_val = Spool[((size_t)bh * n_blocks_x + xb) * n_other + m];
+      db_val = DBt[((size_t)bh * n_other + m) * n_blocks_x + xb];
+    }
     asm volatile("" ::: "memory");      // the A operand is re-read every iteration: no hoisting into registers
     // every accumulator of a lane belongs to column o0 + l32; its rows are spread over the
     // registers, the row tiles and the two half-waves
@@ -133,45 +148,19 @@ __global__ __launch_bounds__(NT, RSA_DEV_OCC) void deviation_kernel(Dims dm, con
     }
     float dv = (dv4[0] + dv4[1]) + (dv4[2] + dv4[3]);
     dv += __shfl_xor(dv, 32);
-    if (hf == 0 && o0 + l32 < n_other) orow[o0 + l32] = dv * outscale;
+    if constexpr (GATE) {
+      const bool pred = o0 + l32 < n_other && fabsf(s_val) > dv * outscale + db_val;
+      const unsigned long long word = __ballot(pred);
+      if (lane == 0) Mc_bits[((size_t)bh * n_blocks_x + xb) * dm.w + o0 / 32] = (uint32_t)word;
+    } else {
+      if (hf == 0 && o0 + l32 < n_other) orow[o0 + l32] = dv * outscale;
+    }
   };
   u32x4 b0[KS], b1[KS];
   if (32 * wave < n_other) load_vectors(b0, 32 * wave);
   for (int o0 = 32 * wave; o0 < n_other; o0 += 64 * NW) {
     iteration(b0, b1, o0);
     if (o0 + 32 * NW < n_other) iteration(b1, b0, o0 + 32 * NW);
-  }
-}
-
-// M_c bits from Spool, DA [N][M] and DBt [M][N]; 32 x 32 tiles, DBt transposed through LDS.
-__global__ __launch_bounds__(256) void gate_kernel(Dims dm, GaprArgs a) {
-  __shared__ float tile[32][33];
-  const int bh = blockIdx.z;
-  const int m0 = blockIdx.x * 32, n0 = blockIdx.y * 32;
-  const int tx = threadIdx.x % 32, ty = threadIdx.x / 32;
-  const float* DBt = a.DBt + (size_t)bh * dm.m * dm.n;
-  const float* DA = a.DA + (size_t)bh * dm.n * dm.m;
-  const float* S = a.Spool + (size_t)bh * dm.n * dm.m;
-#pragma unroll
-  for (int it = 0; it < 4; ++it) {
-    const int mm = m0 + ty + 8 * it, nn = n0 + tx;
-    tile[ty + 8 * it][tx] = (mm < dm.m && nn < dm.n) ? DBt[(size_t)mm * dm.n + nn] : 0.f;
-  }
-  __syncthreads();
-#pragma unroll
-  for (int it = 0; it < 4; ++it) {
-    const int noff = ty + 8 * it;
-    const int nn = n0 + noff, mm = m0 + tx;
-    bool pred = false;
-    if (nn < dm.n && mm < dm.m) {
-      const size_t idx = (size_t)nn * dm.m + mm;
-      pred = fabsf(S[idx]) > DA[idx] + tile[tx][noff];
-    }
-    const unsigned long long bal = __ballot(pred);
-    if (tx == 0 && nn < dm.n) {
-      const uint32_t word = (threadIdx.x & 32) ? (uint32_t)(bal >> 32) : (uint32_t)bal;
-      a.Mc_bits[((size_t)bh * dm.n + nn) * dm.w + blockIdx.x] = word;
-    }
   }
 }
 
@@ -190,9 +179,12 @@ template <int D, int BLK>
 hipError_t launch_gapr_t(const Dims& dm, const GaprArgs& a, hipStream_t s) {
   const int bh = dm.batch * dm.heads;
   constexpr int NT = RSA_DEV_NT;
-  hipLaunchKernelGGL((deviation_kernel<D, BLK, NT>), dim3(dm.n, bh), dim3(NT), 0, s, dm, a.Q, a.Qp, dm.n, a.Kpb, dm.m, a.DA);
-  hipLaunchKernelGGL((deviation_kernel<D, BLK, NT>), dim3(dm.m, bh), dim3(NT), 0, s, dm, a.K, a.Kp, dm.m, a.Qpb, dm.n, a.DBt);
-  hipLaunchKernelGGL(gate_kernel, dim3(dm.w, (dm.n + 31) / 32, bh), dim3(256), 0, s, dm, a);
+  // key side first (DBt [M][N] to the workspace), then the query side, which turns its deviations into
+  // the bits of M_c on the spot
+  hipLaunchKernelGGL((deviation_kernel<D, BLK, NT, false>), dim3(dm.m, bh), dim3(NT), 0, s, dm, a.K, a.Kp, dm.m, a.Qpb, dm.n,
+                     a.DBt, nullptr, nullptr, nullptr);
+  hipLaunchKernelGGL((deviation_kernel<D, BLK, NT, true>), dim3(dm.n, bh), dim3(NT), 0, s, dm, a.Q, a.Qp, dm.n, a.Kpb, dm.m,
+                     nullptr, a.Spool, a.DBt, a.Mc_bits);
   return hipGetLastError();
 }
 

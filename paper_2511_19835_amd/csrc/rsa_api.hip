@@ -47,7 +47,7 @@ inline size_t align256(size_t x) { return (x + 255) & ~(size_t)255; }
 
 // Carving of the pooling workspace; every piece 256-byte aligned.
 struct PoolWs {
-  size_t qpb, kpb, da, dbt, total;
+  size_t qpb, kpb, dbt, total;
 };
 PoolWs pool_ws_layout(const Dims& d) {
   size_t bh = (size_t)d.batch * d.heads;
@@ -55,7 +55,6 @@ PoolWs pool_ws_layout(const Dims& d) {
   size_t off = 0;
   w.qpb = off; off += align256(bh * rsa::gate_operand_vectors(d.n) * d.d * sizeof(uint16_t));
   w.kpb = off; off += align256(bh * rsa::gate_operand_vectors(d.m) * d.d * sizeof(uint16_t));
-  w.da = off;   off += align256(bh * (size_t)d.n * d.m * sizeof(float));
   w.dbt = off;  off += align256(bh * (size_t)d.n * d.m * sizeof(float));
   w.total = off;
   return w;
@@ -213,7 +212,7 @@ int rsa_pool(const rsa_shape* shape, const void* Q, const void* K, const void* V
   ga.Q = (const uint16_t*)Q; ga.K = (const uint16_t*)K;
   ga.Qp = Qp; ga.Kp = Kp;
   ga.Qpb = pa.Qpb; ga.Kpb = pa.Kpb; ga.Spool = Spool;
-  ga.DA = (float*)(wsb + wl.da); ga.DBt = (float*)(wsb + wl.dbt);
+  ga.DBt = (float*)(wsb + wl.dbt);
   ga.Mc_bits = Mc_bits; ga.mode = gapr_mode;
   if (rsa::launch_gapr(d, ga, s) != hipSuccess) return RSA_E_LAUNCH;
   return RSA_OK;

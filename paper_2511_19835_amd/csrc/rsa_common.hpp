@@ -87,7 +87,7 @@ struct GaprArgs {
   const float *Qp, *Kp;    // fp32 pooled vectors (the centre of each token block)
   const uint16_t *Qpb, *Kpb;
   const float* Spool;
-  float *DA, *DBt;         // [b][h][N][M], [b][h][M][N]
+  float* DBt;              // key-side deviations, [b][h][M][N] (workspace)
   uint32_t* Mc_bits;
   int mode;
 };
