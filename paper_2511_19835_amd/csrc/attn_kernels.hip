@@ -908,60 +908,70 @@ __global__ __launch_bounds__(512, 1) void attn_kernel(Dims dm, AttnArgs a, Sched
 // Pooled compensation (Alg. 1 step 21): C[n][:] = sum over blocks m that are not kept and
 // have their M_c bit set of A^pool[n][m] * v^pool[m][:], all fp32, blocks in ascending order.
 // Most blocks are not compensated (the gate is off, or the block is kept), so the sum runs over
-// the set bits only. One wave per query block: lane l looks at block 64 s + l of slot s (its
-// bit, its weight: one coalesced read of the row of A^pool), a ballot gives the slot's
-// compensated blocks, and for each of them, eight at a time so that their loads are in flight
-// together, the weight is broadcast from its lane and the row of v^pool (L2 resident) is added,
-// every lane owning D/64 channels. Padding entries of a group of eight carry weight 0 and add
-// exactly nothing.
+// the set bits only. One wave per query block. The lanes hold the row's words of (not kept and
+// gate); slot by slot (64 blocks) a ballot-style prefix count packs the indices of the set bits
+// into the wave's list in LDS, ascending. Then lane l takes entry 64 g + l of the list with its
+// weight (one gather from the row of A^pool), and the entries are walked sixteen at a time --
+// index and weight broadcast from their lane, the sixteen rows of v^pool (L2 resident) in flight
+// together, every lane owning D/64 channels. Entries past the end of the list carry weight 0 and
+// add exactly nothing. `lds`: 2 bytes per block of a row for each of the four waves.
 template <int D>
-__global__ __launch_bounds__(256) void compensation_kernel(Dims dm, AttnArgs a) {
+__device__ __forceinline__ void compensate_rows(const Dims& dm, const AttnArgs& a, int first_row, int bh, uint32_t* lds) {
   constexpr int CPL = D / 64;                    // channels per lane
-  constexpr int U = 8;                           // blocks per group
-  const int lane = threadIdx.x % 64;
-  const int n = blockIdx.x * 4 + (int)(threadIdx.x / 64), bh = blockIdx.y;
-  if (n >= dm.n) return;                         // no barriers in this kernel
+  constexpr int U = 16;                          // entries per batch
+  const int lane = threadIdx.x % 64, wave = threadIdx.x / 64;
+  const int n = first_row + wave;
+  if (n >= dm.n) return;                         // no workgroup barriers in this function
   const size_t row = (size_t)bh * dm.n + n;
   const uint32_t* kept = a.mask_bits + row * dm.w;
   const uint32_t* gate = a.Mc_bits + row * dm.w;
   const float* A = a.Apool + row * dm.m;
   const float* Vp = a.Vp + (size_t)bh * dm.m * D + lane;
+  const int slots = (dm.m + 63) / 64;
+  uint16_t* lst = reinterpret_cast<uint16_t*>(lds) + (size_t)wave * slots * 64;
+  // words lane and 64 + lane of the row (a row has at most RSA_MAX_BLOCKS / 32 = 128 of them)
+  uint32_t w0 = 0u, w1 = 0u;
+  if (lane < dm.w) w0 = ~kept[lane] & gate[lane];
+  if (64 + lane < dm.w) w1 = ~kept[64 + lane] & gate[64 + lane];
+  int total = 0;
+  for (int s = 0; s < slots; ++s) {
+    const uint32_t lo = s < 32 ? __builtin_amdgcn_readlane(w0, (2 * s) & 63) : __builtin_amdgcn_readlane(w1, (2 * s) & 63);
+    const uint32_t hi = s < 32 ? __builtin_amdgcn_readlane(w0, (2 * s + 1) & 63) : __builtin_amdgcn_readlane(w1, (2 * s + 1) & 63);
+    unsigned long long bits = ((unsigned long long)hi << 32) | lo;
+    const int left = dm.m - 64 * s;              // blocks of this slot that exist
+    if (left < 64) bits &= (1ull << left) - 1ull;
+    const int before = __builtin_amdgcn_mbcnt_hi((uint32_t)(bits >> 32), __builtin_amdgcn_mbcnt_lo((uint32_t)bits, 0));
+    if ((bits >> lane) & 1ull) lst[total + before] = (uint16_t)(64 * s + lane);
+    total += __popcll(bits);
+  }
+  // the list was written by other lanes of this wave
+  __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
+  __builtin_amdgcn_wave_barrier();
+  __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
   float acc[CPL];
 #pragma unroll
   for (int c = 0; c < CPL; ++c) acc[c] = 0.f;
-  const int slots = (dm.m + 63) / 64;
-  // this lane's block of a slot: is it compensated, and its weight (read a slot ahead of its use)
-  auto look = [&](int s, bool& on, float& wl) __attribute__((always_inline)) {
-    const int m = 64 * s + lane, word = 2 * s + (lane >> 5);
-    on = false;
-    wl = 0.f;
-    if (m < dm.m) {
-      on = ((~kept[word] & gate[word]) >> (lane & 31)) & 1u;
-      if (on) wl = A[m];
+  for (int g0 = 0; g0 < total; g0 += 64) {
+    int mine = 0;
+    float wl = 0.f;
+    if (g0 + lane < total) {
+      mine = lst[g0 + lane];
+      wl = A[mine];
     }
-  };
-  bool on_next;
-  float wl_next;
-  look(0, on_next, wl_next);
-  for (int s = 0; s < slots; ++s) {
-    const bool on = on_next;
-    const float wl = wl_next;
-    if (s + 1 < slots) look(s + 1, on_next, wl_next);
-    unsigned long long todo = __ballot(on);
-    while (todo) {
+    const int here = min(64, total - g0);
+    for (int u0 = 0; u0 < here; u0 += U) {
       int src[U];
       float wt[U];
 #pragma unroll
       for (int u = 0; u < U; ++u) {
-        src[u] = todo ? __builtin_ctzll(todo) : 0;           // wave-uniform
-        wt[u] = todo ? __shfl(wl, src[u]) : 0.f;
-        todo &= todo - 1;                                    // 0 stays 0
+        src[u] = __builtin_amdgcn_readlane(mine, u0 + u);      // wave-uniform; 0 with weight 0 past the end
+        wt[u] = __builtin_bit_cast(float, __builtin_amdgcn_readlane(__builtin_bit_cast(int, wl), u0 + u));
       }
       float v[U][CPL];
 #pragma unroll
       for (int u = 0; u < U; ++u)
 #pragma unroll
-        for (int c = 0; c < CPL; ++c) v[u][c] = Vp[(size_t)(64 * s + src[u]) * D + 64 * c];
+        for (int c = 0; c < CPL; ++c) v[u][c] = Vp[(size_t)src[u] * D + 64 * c];
 #pragma unroll
       for (int u = 0; u < U; ++u)
 #pragma unroll
@@ -970,6 +980,12 @@ __global__ __launch_bounds__(256) void compensation_kernel(Dims dm, AttnArgs a) 
   }
 #pragma unroll
   for (int c = 0; c < CPL; ++c) a.comp[row * D + lane + 64 * c] = acc[c];
+}
+
+template <int D>
+__global__ __launch_bounds__(256) void compensation_kernel(Dims dm, AttnArgs a) {
+  extern __shared__ uint32_t side_lds[];
+  compensate_rows<D>(dm, a, blockIdx.x * 4, blockIdx.y, side_lds);
 }
 
 // Launch order of the video query blocks of one (batch, head): sorted by their first three
@@ -1039,12 +1055,14 @@ struct DealArgs {
   int cap, n_queues, slots_per_xcd;
   int n_dense, dense_per_bh, dense_first;
 };
+constexpr int kDealSegment = 2048;   // items of a queue staged in LDS at a time: two int32 each
 template <int SPB>
-__global__ __launch_bounds__(256) void schedule_kernel(Dims dm, AttnArgs a, DealArgs da) {
-  constexpr int SEG = 2048;
+__device__ __forceinline__ void deal_queue(const Dims& dm, const AttnArgs& a, const DealArgs& da, int q, uint32_t* lds) {
+  constexpr int SEG = kDealSegment;
   constexpr int kStrictTail = 128;
-  __shared__ int32_t rec[SEG], len[SEG];
-  const int q = blockIdx.x, tid = threadIdx.x, lane = tid % 64;
+  int32_t* rec = reinterpret_cast<int32_t*>(lds);
+  int32_t* len = rec + SEG;
+  const int tid = threadIdx.x, lane = tid % 64;
   const bool dense_all = (a.flags & RSA_DENSE) != 0;
   const int bh_total = dm.batch * dm.heads;
   // items of this queue: dense items d = q, q + n_queues, ...; then for every head the positions
@@ -1107,6 +1125,25 @@ __global__ __launch_bounds__(256) void schedule_kernel(Dims dm, AttnArgs a, Deal
   }
 }
 
+template <int SPB>
+__global__ __launch_bounds__(256) void schedule_kernel(Dims dm, AttnArgs a, DealArgs da) {
+  extern __shared__ uint32_t side_lds[];
+  deal_queue<SPB>(dm, a, da, blockIdx.x, side_lds);
+}
+
+// Both of the above in one launch (neither needs the other's result, and the few workgroups that deal
+// the queues would otherwise have the chip to themselves): plane 0 of the grid deals queue blockIdx.x,
+// plane 1 + bh compensates the rows of (batch, head) bh. The dealing workgroups are dispatched first.
+template <int D, int SPB>
+__global__ __launch_bounds__(256) void compensation_schedule_kernel(Dims dm, AttnArgs a, DealArgs da) {
+  extern __shared__ uint32_t side_lds[];
+  if (blockIdx.y == 0) {
+    if ((int)blockIdx.x < da.n_queues) deal_queue<SPB>(dm, a, da, blockIdx.x, side_lds);   // uniform over the workgroup
+    return;
+  }
+  compensate_rows<D>(dm, a, blockIdx.x * 4, (int)blockIdx.y - 1, side_lds);
+}
+
 // Sizes of the schedule for `n_wg` resident workgroups of NGRP groups (host and launcher agree on them).
 struct SchedShape {
   int n_queues, slots_per_xcd, cap, chunk, n_items, n_dense, dense_per_bh, dense_first;
@@ -1143,16 +1180,27 @@ hipError_t launch_attn_t(const Dims& dm, const AttnArgs& a, const AttnSched& ws,
   sc.n_dense = sh.n_dense;
   sc.dense_per_bh = sh.dense_per_bh > 0 ? sh.dense_per_bh : 1;
   sc.dense_first = sh.dense_first;
-  if (!dense_all && (a.flags & RSA_COMPENSATE))
-    hipLaunchKernelGGL((compensation_kernel<D>), dim3((dm.n + 3) / 4, bh), dim3(256), 0, s, dm, a);
+  const bool compensate = !dense_all && (a.flags & RSA_COMPENSATE);
+  const bool deal = ws.table && sh.n_queues * 64 <= RSA_ATTN_SCHED_SLOTS && (size_t)sh.n_queues * 64 * sh.cap <= ws.table_entries;
+  const dim3 comp_grid((dm.n + 3) / 4, bh);
+  const unsigned comp_lds = 4u * (unsigned)((dm.m + 63) / 64) * 64u * 2u;    // four lists of 16-bit block indices
+  const unsigned deal_lds = 2u * kDealSegment * 4u;
   if (!dense_all && a.row_order) hipLaunchKernelGGL(row_order_kernel, dim3(bh), dim3(1024), 0, s, dm, a);
-  if (ws.table && sh.n_queues * 64 <= RSA_ATTN_SCHED_SLOTS && (size_t)sh.n_queues * 64 * sh.cap <= ws.table_entries) {
+  if (deal) {
     DealArgs da;
     da.table = ws.table; da.nitems = ws.nitems; da.total = ws.total;
     da.cap = sh.cap; da.n_queues = sh.n_queues; da.slots_per_xcd = sh.slots_per_xcd;
     da.n_dense = sh.n_dense; da.dense_per_bh = sc.dense_per_bh; da.dense_first = sh.dense_first;
-    hipLaunchKernelGGL((schedule_kernel<C::SPB>), dim3(sh.n_queues), dim3(256), 0, s, dm, a, da);
+    if (compensate && sh.n_queues <= (int)comp_grid.x)
+      hipLaunchKernelGGL((compensation_schedule_kernel<D, C::SPB>), dim3(comp_grid.x, bh + 1), dim3(256),
+                         comp_lds > deal_lds ? comp_lds : deal_lds, s, dm, a, da);
+    else {
+      if (compensate) hipLaunchKernelGGL((compensation_kernel<D>), comp_grid, dim3(256), comp_lds, s, dm, a);
+      hipLaunchKernelGGL((schedule_kernel<C::SPB>), dim3(sh.n_queues), dim3(256), deal_lds, s, dm, a, da);
+    }
     sc.table = ws.table; sc.nitems = ws.nitems; sc.total = ws.total; sc.cap = sh.cap;
+  } else if (compensate) {
+    hipLaunchKernelGGL((compensation_kernel<D>), comp_grid, dim3(256), comp_lds, s, dm, a);
   }
   hipLaunchKernelGGL((attn_kernel<D, BLK>), dim3((unsigned)n_wg), dim3(C::NTHR), 0, s, dm, a, sc);
   return hipGetLastError();
