@@ -58,7 +58,14 @@ __global__ __launch_bounds__(NT, RSA_DEV_OCC) void deviation_kernel(Dims dm, con
   constexpr int NW = NT / 64;                    // waves per workgroup
   constexpr int RPP = NT / CPR;                  // rows staged per pass of the workgroup
   __shared__ u32x4 atile[BLK * CPR];
-  const int xb = blockIdx.x, bh = blockIdx.y;
+  // Workgroup i runs on XCD i % 8. Each XCD takes a contiguous eighth of the (batch, head, block)
+  // range, so that token blocks that are neighbours run on the same XCD at about the same time: the
+  // query side reads DBt[m][n] for a fixed n, 32 neighbouring n to a 128-byte line, which then
+  // comes into one L2 once instead of into all eight.
+  const int total = n_blocks_x * dm.batch * dm.heads;
+  const int xcd = blockIdx.x % 8, q8 = total / 8, r8 = total % 8;
+  const int item = xcd * q8 + (xcd < r8 ? xcd : r8) + (int)blockIdx.x / 8;
+  const int xb = item % n_blocks_x, bh = item / n_blocks_x;
   const int b = bh / dm.heads, h = bh % dm.heads;
   const int wave = threadIdx.x / 64, lane = threadIdx.x % 64;
   const int l32 = lane % 32, hf = lane / 32;
@@ -181,9 +188,9 @@ hipError_t launch_gapr_t(const Dims& dm, const GaprArgs& a, hipStream_t s) {
   constexpr int NT = RSA_DEV_NT;
   // key side first (DBt [M][N] to the workspace), then the query side, which turns its deviations into
   // the bits of M_c on the spot
-  hipLaunchKernelGGL((deviation_kernel<D, BLK, NT, false>), dim3(dm.m, bh), dim3(NT), 0, s, dm, a.K, a.Kp, dm.m, a.Qpb, dm.n,
+  hipLaunchKernelGGL((deviation_kernel<D, BLK, NT, false>), dim3(dm.m * bh), dim3(NT), 0, s, dm, a.K, a.Kp, dm.m, a.Qpb, dm.n,
                      a.DBt, nullptr, nullptr, nullptr);
-  hipLaunchKernelGGL((deviation_kernel<D, BLK, NT, true>), dim3(dm.n, bh), dim3(NT), 0, s, dm, a.Q, a.Qp, dm.n, a.Kpb, dm.m,
+  hipLaunchKernelGGL((deviation_kernel<D, BLK, NT, true>), dim3(dm.n * bh), dim3(NT), 0, s, dm, a.Q, a.Qp, dm.n, a.Kpb, dm.m,
                      nullptr, a.Spool, a.DBt, a.Mc_bits);
   return hipGetLastError();
 }
