@@ -10,7 +10,8 @@
 // (gain and error both divided by c_n c_m). Each deviation is a skinny GEMM of a token
 // block against all pooled vectors of the other side, so the cost is tokens x blocks x d.
 //
-// deviation_kernel: one workgroup per token block. The block is read once, centred on its
+// deviation_kernel: one workgroup per token block. The block is read once (on the key side the
+// launch pools it as well: the only pass over K of the whole preparation), centred on its
 // pooled vector (x_i - x^pool, fp32 subtraction, rounded to fp16) and parked in LDS; every
 // wave then walks the pooled vectors of the other side 32 at a time against the whole centred
 // block (the MFMA A operand, read from LDS just ahead of each MFMA), so the accumulators hold
@@ -46,9 +47,14 @@ __device__ __forceinline__ int swizzled(int r, int c) { return r * CPR + (c ^ ((
 // with the pooled score S[n][m] and the key-side deviation DBt[m][n] of the first launch (one word each
 // per lane and iteration, asked for at the start of the iteration) the lane decides its bit of M_c, and
 // a ballot makes the mask word of the iteration.
-template <int D, int BLK, int NT, bool GATE>
+// POOL (key side only): the launch also makes the pooled vector of its block -- it holds the whole block in
+// registers before it centres it -- and writes it (fp32, and the fp16 operand copy) for the kernels that
+// follow, with the arithmetic of pool_qk_kernel (same thread-to-row mapping, same order of additions), so
+// the separate pooling pass over K is not needed.
+template <int D, int BLK, int NT, bool GATE, bool POOL>
 __global__ __launch_bounds__(NT, RSA_DEV_OCC) void deviation_kernel(Dims dm, const uint16_t* __restrict__ X,
-                                                           const float* __restrict__ Xpool, int n_blocks_x,
+                                                           const float* __restrict__ Xpool, float* __restrict__ Xpool_out,
+                                                           uint16_t* __restrict__ Xpool_f16_out, int n_blocks_x,
                                                            const uint16_t* __restrict__ PB,
                                                            int n_other, float* __restrict__ out,
                                                            const float* __restrict__ Spool,
@@ -76,15 +82,45 @@ __global__ __launch_bounds__(NT, RSA_DEV_OCC) void deviation_kernel(Dims dm, con
   // ---- stage the centred block: thread -> chunk column tid % CPR, rows tid / CPR + RPP*i ----
   {
     const int cc = threadIdx.x % CPR, r0 = threadIdx.x / CPR;
-    const float* mp = Xpool + ((size_t)bh * n_blocks_x + xb) * D + 8 * cc;
-    const floatx4 m0 = *reinterpret_cast<const floatx4*>(mp);
-    const floatx4 m1 = *reinterpret_cast<const floatx4*>(mp + 4);
     u32x4 raw[BLK / RPP];
 #pragma unroll
     for (int i = 0; i < BLK / RPP; ++i) {
       const int r = r0 + RPP * i;
       const int rr = r < count ? r : count - 1;                  // stay inside the tensor; zeroed below
       raw[i] = *reinterpret_cast<const u32x4*>(Xb + (t0 + rr) * dm.st + 8 * cc);
+    }
+    floatx4 m0, m1;
+    if constexpr (POOL) {
+      static_assert(NT == 256 && RPP * D * 4 <= BLK * CPR * 16, "the mapping of pool_qk_kernel; its partial sums fit the tile");
+      __shared__ __align__(16) float mean_lds[D];
+      float (*red)[D] = reinterpret_cast<float (*)[D]>(atile);   // the tile is written after the sums have been read
+      float acc[8] = {0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f};
+#pragma unroll
+      for (int i = 0; i < BLK / RPP; ++i) {
+        uint4 v = make_uint4(0, 0, 0, 0);
+        if (r0 + RPP * i < count) v = make_uint4(raw[i].x, raw[i].y, raw[i].z, raw[i].w);
+        accumulate8(acc, v);
+      }
+#pragma unroll
+      for (int e = 0; e < 8; ++e) red[r0][cc * 8 + e] = acc[e];
+      __syncthreads();
+      if (threadIdx.x < D) {
+        float sum = 0.f;
+#pragma unroll
+        for (int r = 0; r < RPP; ++r) sum += red[r][threadIdx.x];
+        const float mean = sum / (float)count;
+        mean_lds[threadIdx.x] = mean;
+        Xpool_out[((size_t)bh * n_blocks_x + xb) * D + threadIdx.x] = mean;
+        Xpool_f16_out[(size_t)bh * gate_operand_vectors(n_blocks_x) * D + gate_operand_offset<D>(xb, threadIdx.x)] = to_f16_bits_sat(mean);
+      }
+      __syncthreads();
+      m0 = *reinterpret_cast<const floatx4*>(mean_lds + 8 * cc);
+      m1 = *reinterpret_cast<const floatx4*>(mean_lds + 8 * cc + 4);
+      __syncthreads();                                             // every read of the sums is done
+    } else {
+      const float* mp = Xpool + ((size_t)bh * n_blocks_x + xb) * D + 8 * cc;
+      m0 = *reinterpret_cast<const floatx4*>(mp);
+      m1 = *reinterpret_cast<const floatx4*>(mp + 4);
     }
 #pragma unroll
     for (int i = 0; i < BLK / RPP; ++i) {
@@ -183,29 +219,51 @@ __global__ void fill_bits_kernel(Dims dm, uint32_t* bits, uint32_t value) {
 }
 
 template <int D, int BLK>
-hipError_t launch_gapr_t(const Dims& dm, const GaprArgs& a, hipStream_t s) {
+hipError_t launch_gapr_keys_t(const Dims& dm, const GaprArgs& a, hipStream_t s) {
   const int bh = dm.batch * dm.heads;
   constexpr int NT = RSA_DEV_NT;
-  // key side first (DBt [M][N] to the workspace), then the query side, which turns its deviations into
-  // the bits of M_c on the spot
-  hipLaunchKernelGGL((deviation_kernel<D, BLK, NT, false>), dim3(dm.m * bh), dim3(NT), 0, s, dm, a.K, a.Kp, dm.m, a.Qpb, dm.n,
-                     a.DBt, nullptr, nullptr, nullptr);
-  hipLaunchKernelGGL((deviation_kernel<D, BLK, NT, true>), dim3(dm.n * bh), dim3(NT), 0, s, dm, a.Q, a.Qp, dm.n, a.Kpb, dm.m,
-                     nullptr, a.Spool, a.DBt, a.Mc_bits);
+  // DBt [M][N] to the workspace
+  if (a.Kp_out)
+    hipLaunchKernelGGL((deviation_kernel<D, BLK, NT, false, true>), dim3(dm.m * bh), dim3(NT), 0, s, dm, a.K, nullptr, a.Kp_out,
+                       a.Kpb_out, dm.m, a.Qpb, dm.n, a.DBt, nullptr, nullptr, nullptr);
+  else
+    hipLaunchKernelGGL((deviation_kernel<D, BLK, NT, false, false>), dim3(dm.m * bh), dim3(NT), 0, s, dm, a.K, a.Kp, nullptr,
+                       nullptr, dm.m, a.Qpb, dm.n, a.DBt, nullptr, nullptr, nullptr);
+  return hipGetLastError();
+}
+template <int D, int BLK>
+hipError_t launch_gapr_queries_t(const Dims& dm, const GaprArgs& a, hipStream_t s) {
+  const int bh = dm.batch * dm.heads;
+  constexpr int NT = RSA_DEV_NT;
+  // turns its deviations into the bits of M_c on the spot
+  hipLaunchKernelGGL((deviation_kernel<D, BLK, NT, true, false>), dim3(dm.n * bh), dim3(NT), 0, s, dm, a.Q, a.Qp, nullptr, nullptr,
+                     dm.n, a.Kpb, dm.m, nullptr, a.Spool, a.DBt, a.Mc_bits);
   return hipGetLastError();
 }
 
 }  // namespace
+
+hipError_t launch_gapr_keys(const Dims& dm, const GaprArgs& a, hipStream_t s) {
+  if (dm.d == 128 && dm.blk == 128) return launch_gapr_keys_t<128, 128>(dm, a, s);
+  if (dm.d == 128 && dm.blk == 64) return launch_gapr_keys_t<128, 64>(dm, a, s);
+  if (dm.d == 64 && dm.blk == 128) return launch_gapr_keys_t<64, 128>(dm, a, s);
+  return launch_gapr_keys_t<64, 64>(dm, a, s);
+}
+
+hipError_t launch_gapr_queries(const Dims& dm, const GaprArgs& a, hipStream_t s) {
+  if (dm.d == 128 && dm.blk == 128) return launch_gapr_queries_t<128, 128>(dm, a, s);
+  if (dm.d == 128 && dm.blk == 64) return launch_gapr_queries_t<128, 64>(dm, a, s);
+  if (dm.d == 64 && dm.blk == 128) return launch_gapr_queries_t<64, 128>(dm, a, s);
+  return launch_gapr_queries_t<64, 64>(dm, a, s);
+}
 
 hipError_t launch_gapr(const Dims& dm, const GaprArgs& a, hipStream_t s) {
   if (a.mode != 1) {
     hipLaunchKernelGGL(fill_bits_kernel, dim3(256), dim3(256), 0, s, dm, a.Mc_bits, a.mode == 2 ? 0xffffffffu : 0u);
     return hipGetLastError();
   }
-  if (dm.d == 128 && dm.blk == 128) return launch_gapr_t<128, 128>(dm, a, s);
-  if (dm.d == 128 && dm.blk == 64) return launch_gapr_t<128, 64>(dm, a, s);
-  if (dm.d == 64 && dm.blk == 128) return launch_gapr_t<64, 128>(dm, a, s);
-  return launch_gapr_t<64, 64>(dm, a, s);
+  const hipError_t e = launch_gapr_keys(dm, a, s);
+  return e != hipSuccess ? e : launch_gapr_queries(dm, a, s);
 }
 
 }  // namespace rsa

@@ -10,15 +10,6 @@
 namespace rsa {
 namespace {
 
-__device__ inline void accumulate8(float (&acc)[8], const uint4& v) {
-  const uint32_t w[4] = {v.x, v.y, v.z, v.w};
-#pragma unroll
-  for (int i = 0; i < 4; ++i) {
-    acc[2 * i] += bf16_bits_to_float(w[i] & 0xffffu);
-    acc[2 * i + 1] += bf16_bits_to_float(w[i] >> 16);
-  }
-}
-
 // Reduce the per-thread partial sums over the row groups and write the block mean
 // (fp32) and, optionally, an fp16 copy (saturated; the gate GEMMs' pooled operand).
 template <int D, int RPP>
@@ -134,7 +125,7 @@ template <int D, int BLK>
 hipError_t launch_pool_t(const Dims& dm, const PoolArgs& a, hipStream_t s) {
   const dim3 block(256);
   if (a.Q && a.K)    // values only: the caller keeps the pooled queries / keys of an earlier call
-    hipLaunchKernelGGL((pool_qk_kernel<D, BLK>), dim3(dm.m, dm.batch * dm.heads, 2), block, 0, s, dm, a);
+    hipLaunchKernelGGL((pool_qk_kernel<D, BLK>), dim3(dm.m, dm.batch * dm.heads, a.skip_k ? 1 : 2), block, 0, s, dm, a);
   hipLaunchKernelGGL((pool_v_kernel<D, BLK>), dim3(dm.m, dm.batch * dm.heads, 1), block, 0, s, dm, a);
   return hipGetLastError();
 }

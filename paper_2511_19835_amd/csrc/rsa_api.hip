@@ -201,12 +201,9 @@ int rsa_pool(const rsa_shape* shape, const void* Q, const void* K, const void* V
   pa.Qp = Qp; pa.Kp = Kp; pa.Vp = Vp; pa.Vt = (uint16_t*)Vt;
   pa.Qpb = (uint16_t*)(wsb + wl.qpb);
   pa.Kpb = (uint16_t*)(wsb + wl.kpb);
+  // with the gate on, the launch that reads the key blocks for their deviations pools them as well
+  pa.skip_k = gapr_mode == 1;
   if (rsa::launch_pool(d, pa, s) != hipSuccess) return RSA_E_LAUNCH;
-
-  rsa::ScoreArgs sa;
-  sa.K = (const uint16_t*)K; sa.Qp = Qp; sa.Kp = Kp;
-  sa.Spool = Spool; sa.Apool = Apool; sa.Lmass = Lmass;
-  if (rsa::launch_scores(d, sa, s) != hipSuccess) return RSA_E_LAUNCH;
 
   rsa::GaprArgs ga;
   ga.Q = (const uint16_t*)Q; ga.K = (const uint16_t*)K;
@@ -214,6 +211,20 @@ int rsa_pool(const rsa_shape* shape, const void* Q, const void* K, const void* V
   ga.Qpb = pa.Qpb; ga.Kpb = pa.Kpb; ga.Spool = Spool;
   ga.DBt = (float*)(wsb + wl.dbt);
   ga.Mc_bits = Mc_bits; ga.mode = gapr_mode;
+  if (gapr_mode == 1) {
+    ga.Kp_out = Kp; ga.Kpb_out = pa.Kpb;
+    if (rsa::launch_gapr_keys(d, ga, s) != hipSuccess) return RSA_E_LAUNCH;
+  }
+
+  rsa::ScoreArgs sa;
+  sa.K = (const uint16_t*)K; sa.Qp = Qp; sa.Kp = Kp;
+  sa.Spool = Spool; sa.Apool = Apool; sa.Lmass = Lmass;
+  if (rsa::launch_scores(d, sa, s) != hipSuccess) return RSA_E_LAUNCH;
+
+  if (gapr_mode == 1) {
+    if (rsa::launch_gapr_queries(d, ga, s) != hipSuccess) return RSA_E_LAUNCH;
+    return RSA_OK;
+  }
   if (rsa::launch_gapr(d, ga, s) != hipSuccess) return RSA_E_LAUNCH;
   return RSA_OK;
 }

@@ -63,6 +63,15 @@ template <int D>
 __host__ __device__ inline size_t gate_operand_offset(int o, int c) {
   return ((((size_t)(o / 32) * (D / 16) + c / 16) * 2 + (c % 16) / 8) * 32 + o % 32) * 8 + c % 8;
 }
+// Adds the eight bf16 values of a 16-byte chunk to eight running sums (the block-mean reduction).
+__device__ inline void accumulate8(float (&acc)[8], const uint4& v) {
+  const uint32_t w[4] = {v.x, v.y, v.z, v.w};
+#pragma unroll
+  for (int i = 0; i < 4; ++i) {
+    acc[2 * i] += bf16_bits_to_float(w[i] & 0xffffu);
+    acc[2 * i + 1] += bf16_bits_to_float(w[i] >> 16);
+  }
+}
 // vectors are padded to a multiple of 32 per (batch, head)
 __host__ __device__ inline size_t gate_operand_vectors(int n) { return (size_t)((n + 31) / 32) * 32; }
 
@@ -72,6 +81,7 @@ struct PoolArgs {
   float *Qp, *Kp, *Vp;
   uint16_t* Vt;
   uint16_t *Qpb, *Kpb;     // optional fp16 copies of the pooled vectors in gate_operand_offset layout
+  bool skip_k = false;     // the pooled keys come from the key-side launch of the gate (launch_gapr_keys)
 };
 hipError_t launch_pool(const Dims& dm, const PoolArgs& a, hipStream_t s);
 
@@ -90,7 +100,14 @@ struct GaprArgs {
   float* DBt;              // key-side deviations, [b][h][M][N] (workspace)
   uint32_t* Mc_bits;
   int mode;
+  float* Kp_out = nullptr;       // launch_gapr_keys: pooled keys, written by the launch that reads the key blocks anyway
+  uint16_t* Kpb_out = nullptr;
 };
+// mode 1 is two launches with the pooled scores between them: the key side (needs Qpb; writes DBt and, when
+// Kp_out is set, the pooled keys) and the query side (needs Kpb, Spool, DBt; writes Mc_bits). launch_gapr runs
+// both (pooled keys given), or fills Mc_bits for the other modes.
+hipError_t launch_gapr_keys(const Dims& dm, const GaprArgs& a, hipStream_t s);
+hipError_t launch_gapr_queries(const Dims& dm, const GaprArgs& a, hipStream_t s);
 hipError_t launch_gapr(const Dims& dm, const GaprArgs& a, hipStream_t s);
 
 struct SelectArgs {
