@@ -649,6 +649,35 @@ def test_implicit_attention_alone(gpu):
         assert torch.equal(got, ref)
 
 
+def test_pooled_tensors_do_not_depend_on_the_gate_mode(gpu):
+    """With the gate on, k^pool comes from the key-side deviation launch instead of the pooling kernel:
+    every pooled tensor and the implicit attention must be bit for bit what gapr_mode 0 (no gate GEMMs,
+    the pooling kernel for Q and K) writes. Shapes with a ragged last video block and text blocks, for
+    each kernel template."""
+    import torch
+    from paper_2511_19835_amd import binding as rb
+    for cfg in (synth.CONFIGS["mid"].with_(heads=2, t_text=200),
+                synth.CONFIGS["tiny"].with_(t_text=70),
+                synth.CONFIGS["mid"].with_(heads=1, head_dim=64, t_text=130),
+                synth.CONFIGS["mid"].with_(heads=1, block=64, t_text=130)):
+        Qb, Kb, Vb = synth.make_inputs(cfg, 5)
+        Q, K, V = (gpu.bits_to_device(x) for x in (Qb, Kb, Vb))
+        buf = rb.allocate(Q, cfg.t_video, cfg.t_text, cfg.block)
+        names = ("Qp", "Kp", "Vp", "Vt", "Spool", "Lmass", "Apool")
+        got = {}
+        for mode in (0, 1):
+            for name in names:
+                t = getattr(buf, name)
+                t.fill_(float("nan")) if t.is_floating_point() else t.zero_()
+            rb.rsa_pool(buf.shape, Q, K, V, buf.Qp, buf.Kp, buf.Vp, buf.Vt, buf.Spool, buf.Apool, buf.Lmass,
+                        buf.Mc_bits, mode, buf.pool_ws)
+            torch.cuda.synchronize()
+            got[mode] = {name: getattr(buf, name).clone() for name in names}
+        for name in names:
+            a, b = got[0][name], got[1][name]
+            assert torch.equal(a.view(torch.uint8), b.view(torch.uint8)), (cfg.name, cfg.head_dim, cfg.block, name)
+
+
 def test_maximum_block_count(gpu):
     """M = RSA_MAX_BLOCKS = 4096 key blocks (64 x 64 x 64 latent grid, block 64, one head of d 64):
     the selection kernel's LDS keys, the launch-order sort and the mask words at their largest."""
