@@ -25,6 +25,7 @@ SOURCES = [
     "select_kernels.hip",
     "adjacency_kernels.hip",
     "reorder_kernels.hip",
+    "attn_side_kernels.hip",
     "attn_kernels.hip",
 ]
 

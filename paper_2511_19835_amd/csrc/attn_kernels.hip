@@ -26,12 +26,13 @@
 // A^pool[n][m] v^pool_m (computed beforehand by compensation_kernel into the workspace).
 //
 // 4*B*B*d flop per (query block, key block) pair against 2*B*d*2 bytes of K/V traffic.
-// row_order_kernel sorts the video query blocks of a head by their first kept key blocks;
+// The small kernels named here are in attn_side_kernels.hip. row_order_kernel sorts the video query blocks of a head by their first kept key blocks;
 // schedule_kernel deals that order (long dense rows first) to the groups so that each XCD
 // (workgroup id modulo 8) owns a contiguous range of it, groups resident together walk similar
 // lists and share K/V tiles in the XCD's L2, and all groups end within one item of each other.
-#include "rsa_common.hpp"
+#include "attn_sched.hpp"
 #include "lds_dma.hpp"
+#include "rsa_common.hpp"
 
 namespace rsa {
 namespace {
@@ -149,14 +150,6 @@ struct SchedArgs {
   int n_items, n_dense;     // all items; the dense ones (text query blocks, or every block under RSA_DENSE) come first
   int dense_per_bh, dense_first;
 };
-
-// Entries of a video query block's list as every kernel here takes them: the count that
-// rsa_select_blocks wrote, held to 1 .. M so that no count, whatever it is, can derail the loops.
-__device__ __forceinline__ int list_length(const AttnArgs& a, const Dims& dm, size_t vrow) {
-  typedef const int32_t __attribute__((address_space(4))) * const_i32_t;     // scalar loads
-  const int c = ((const_i32_t)(uintptr_t)a.count)[vrow];
-  return min(max(c, 1), dm.m);
-}
 
 template <int D, int BLK>
 __global__ __launch_bounds__(512, 1) void attn_kernel(Dims dm, AttnArgs a, SchedArgs sc) {
@@ -905,272 +898,9 @@ __global__ __launch_bounds__(512, 1) void attn_kernel(Dims dm, AttnArgs a, Sched
   if (grp < NGRP / 2) group_barrier();
 }
 
-// Pooled compensation (Alg. 1 step 21): C[n][:] = sum over blocks m that are not kept and
-// have their M_c bit set of A^pool[n][m] * v^pool[m][:], all fp32, blocks in ascending order.
-// Most blocks are not compensated (the gate is off, or the block is kept), so the sum runs over
-// the set bits only. One wave per query block. The lanes hold the row's words of (not kept and
-// gate); slot by slot (64 blocks) a ballot-style prefix count packs the indices of the set bits
-// into the wave's list in LDS, ascending. Then lane l takes entry 64 g + l of the list with its
-// weight (one gather from the row of A^pool), and the entries are walked sixteen at a time --
-// index and weight broadcast from their lane, the sixteen rows of v^pool (L2 resident) in flight
-// together, every lane owning D/64 channels. Entries past the end of the list carry weight 0 and
-// add exactly nothing. `lds`: 2 bytes per block of a row for each of the four waves.
-template <int D>
-__device__ __forceinline__ void compensate_rows(const Dims& dm, const AttnArgs& a, int first_row, int bh, uint32_t* lds) {
-  constexpr int CPL = D / 64;                    // channels per lane
-  constexpr int U = 16;                          // entries per batch
-  const int lane = threadIdx.x % 64, wave = threadIdx.x / 64;
-  const int n = first_row + wave;
-  if (n >= dm.n) return;                         // no workgroup barriers in this function
-  const size_t row = (size_t)bh * dm.n + n;
-  const uint32_t* kept = a.mask_bits + row * dm.w;
-  const uint32_t* gate = a.Mc_bits + row * dm.w;
-  const float* A = a.Apool + row * dm.m;
-  const float* Vp = a.Vp + (size_t)bh * dm.m * D + lane;
-  const int slots = (dm.m + 63) / 64;
-  uint16_t* lst = reinterpret_cast<uint16_t*>(lds) + (size_t)wave * slots * 64;
-  // words lane and 64 + lane of the row (a row has at most RSA_MAX_BLOCKS / 32 = 128 of them)
-  uint32_t w0 = 0u, w1 = 0u;
-  if (lane < dm.w) w0 = ~kept[lane] & gate[lane];
-  if (64 + lane < dm.w) w1 = ~kept[64 + lane] & gate[64 + lane];
-  int total = 0;
-  for (int s = 0; s < slots; ++s) {
-    const uint32_t lo = s < 32 ? __builtin_amdgcn_readlane(w0, (2 * s) & 63) : __builtin_amdgcn_readlane(w1, (2 * s) & 63);
-    const uint32_t hi = s < 32 ? __builtin_amdgcn_readlane(w0, (2 * s + 1) & 63) : __builtin_amdgcn_readlane(w1, (2 * s + 1) & 63);
-    unsigned long long bits = ((unsigned long long)hi << 32) | lo;
-    const int left = dm.m - 64 * s;              // blocks of this slot that exist
-    if (left < 64) bits &= (1ull << left) - 1ull;
-    const int before = __builtin_amdgcn_mbcnt_hi((uint32_t)(bits >> 32), __builtin_amdgcn_mbcnt_lo((uint32_t)bits, 0));
-    if ((bits >> lane) & 1ull) lst[total + before] = (uint16_t)(64 * s + lane);
-    total += __popcll(bits);
-  }
-  // the list was written by other lanes of this wave
-  __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
-  __builtin_amdgcn_wave_barrier();
-  __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
-  float acc[CPL];
-#pragma unroll
-  for (int c = 0; c < CPL; ++c) acc[c] = 0.f;
-  for (int g0 = 0; g0 < total; g0 += 64) {
-    int mine = 0;
-    float wl = 0.f;
-    if (g0 + lane < total) {
-      mine = lst[g0 + lane];
-      wl = A[mine];
-    }
-    const int here = min(64, total - g0);
-    for (int u0 = 0; u0 < here; u0 += U) {
-      int src[U];
-      float wt[U];
-#pragma unroll
-      for (int u = 0; u < U; ++u) {
-        src[u] = __builtin_amdgcn_readlane(mine, u0 + u);      // wave-uniform; 0 with weight 0 past the end
-        wt[u] = __builtin_bit_cast(float, __builtin_amdgcn_readlane(__builtin_bit_cast(int, wl), u0 + u));
-      }
-      float v[U][CPL];
-#pragma unroll
-      for (int u = 0; u < U; ++u)
-#pragma unroll
-        for (int c = 0; c < CPL; ++c) v[u][c] = Vp[(size_t)src[u] * D + 64 * c];
-#pragma unroll
-      for (int u = 0; u < U; ++u)
-#pragma unroll
-        for (int c = 0; c < CPL; ++c) acc[c] = fmaf(wt[u], v[u][c], acc[c]);
-    }
-  }
-#pragma unroll
-  for (int c = 0; c < CPL; ++c) a.comp[row * D + lane + 64 * c] = acc[c];
-}
-
-template <int D>
-__global__ __launch_bounds__(256) void compensation_kernel(Dims dm, AttnArgs a) {
-  extern __shared__ uint32_t side_lds[];
-  compensate_rows<D>(dm, a, blockIdx.x * 4, blockIdx.y, side_lds);
-}
-
-// Launch order of the video query blocks of one (batch, head): sorted by their first three
-// kept key blocks (ties: block index). Workgroups that are resident on an XCD at the same time
-// then walk similar lists and find each other's K/V tiles in that XCD's L2 (on the benchmark
-// inputs the traffic that crosses the fabric drops by 40 %). A heuristic: any permutation gives
-// the same results. One workgroup per (batch, head), bitonic sort of 64-bit keys in LDS.
-__global__ __launch_bounds__(1024) void row_order_kernel(Dims dm, AttnArgs a) {
-  __shared__ uint64_t keys[RSA_MAX_BLOCKS];
-  const int bh = blockIdx.x, tid = threadIdx.x;
-  int P = 1;
-  while (P < dm.n) P <<= 1;
-  for (int i = tid; i < P; i += 1024) {
-    uint64_t k = ~0ull;                                    // padding sorts to the end
-    if (i < dm.n) {
-      const size_t row = (size_t)bh * dm.n + i;
-      const int cnt = a.count[row];
-      const int32_t* lst = a.block_idx + row * dm.m;
-      const uint64_t i0 = cnt > 0 ? lst[0] : 4095, i1 = cnt > 1 ? lst[1] : 4095, i2 = cnt > 2 ? lst[2] : 4095;
-      k = (i0 << 36) | (i1 << 24) | (i2 << 12) | (uint64_t)i;     // every index < RSA_MAX_BLOCKS = 2^12
-    }
-    keys[i] = k;
-  }
-  __syncthreads();
-  for (int k2 = 2; k2 <= P; k2 <<= 1)
-    for (int j = k2 >> 1; j > 0; j >>= 1) {
-      for (int i = tid; i < P; i += 1024) {
-        const int o = i ^ j;
-        if (o > i) {
-          const uint64_t x = keys[i], y = keys[o];
-          if ((x > y) == ((i & k2) == 0)) {
-            keys[i] = y;
-            keys[o] = x;
-          }
-        }
-      }
-      __syncthreads();
-    }
-  for (int i = tid; i < dm.n; i += 1024) a.row_order[(size_t)bh * dm.n + i] = (int32_t)(keys[i] & 4095u);
-}
-
-// Deals the items of one launch to the slots of the persistent attention kernel. One workgroup per
-// queue of 64 slots (the slots of a queue run on one XCD). The queue's items, in launch order: its
-// share of the dense items (text query blocks, or every block under RSA_DENSE: the long ones first),
-// then, head by head, its contiguous range of the row order of the video query blocks. They are
-// dealt in rounds by one wave, lane = slot: in a round every slot whose load (steps so far) is within
-// one item of the lightest takes the next item, in lane order -- neighbouring items go to neighbouring
-// slots at about the same time, so that workgroups resident together walk similar lists, and the
-// loads end within one item of each other whatever the lengths of the rows.
-// Minimum over the 64 lanes of a wave with data-parallel-primitive moves (row shifts inside the rows of
-// 16 lanes, then the two row broadcasts): lane 63 ends up with it. Lanes without a source take INT_MAX.
-__device__ __forceinline__ int wave_min_i32(int v) {
-  constexpr int kMax = 0x7fffffff;
-  v = min(v, __builtin_amdgcn_update_dpp(kMax, v, 0x111, 0xf, 0xf, false));   // row_shr:1
-  v = min(v, __builtin_amdgcn_update_dpp(kMax, v, 0x112, 0xf, 0xf, false));   // row_shr:2
-  v = min(v, __builtin_amdgcn_update_dpp(kMax, v, 0x114, 0xf, 0xf, false));   // row_shr:4
-  v = min(v, __builtin_amdgcn_update_dpp(kMax, v, 0x118, 0xf, 0xf, false));   // row_shr:8
-  v = min(v, __builtin_amdgcn_update_dpp(kMax, v, 0x142, 0xa, 0xf, false));   // row_bcast:15 into rows 1 and 3
-  v = min(v, __builtin_amdgcn_update_dpp(kMax, v, 0x143, 0xc, 0xf, false));   // row_bcast:31 into rows 2 and 3
-  return __builtin_amdgcn_readlane(v, 63);
-}
-
-struct DealArgs {
-  int32_t* table;           // [queues * 64][cap]
-  int32_t* nitems;          // [queues * 64]
-  int32_t* total;           // [queues * 64]
-  int cap, n_queues, slots_per_xcd;
-  int n_dense, dense_per_bh, dense_first;
-};
-constexpr int kDealSegment = 2048;   // items of a queue staged in LDS at a time: two int32 each
-template <int SPB>
-__device__ __forceinline__ void deal_queue(const Dims& dm, const AttnArgs& a, const DealArgs& da, int q, uint32_t* lds) {
-  constexpr int SEG = kDealSegment;
-  constexpr int kStrictTail = 128;
-  int32_t* rec = reinterpret_cast<int32_t*>(lds);
-  int32_t* len = rec + SEG;
-  const int tid = threadIdx.x, lane = tid % 64;
-  const bool dense_all = (a.flags & RSA_DENSE) != 0;
-  const int bh_total = dm.batch * dm.heads;
-  // items of this queue: dense items d = q, q + n_queues, ...; then for every head the positions
-  // [q N / n_queues, (q + 1) N / n_queues) of its row order
-  const int my_dense = q < da.n_dense ? (da.n_dense - q + da.n_queues - 1) / da.n_queues : 0;
-  const int p0 = (int)((long long)q * dm.n / da.n_queues), p1 = (int)((long long)(q + 1) * dm.n / da.n_queues);
-  const int per_head = dense_all ? 0 : p1 - p0;
-  const int n_queue_items = my_dense + per_head * bh_total;
-  // lane = slot u of this queue; the XCD has slots_per_xcd of them in all
-  const bool slot_ok = (q / 8) * 64 + lane < da.slots_per_xcd;
-  const int slot = q * 64 + lane;
-  int load = 0, cnt = 0;
-  for (int seg0 = 0; seg0 < n_queue_items; seg0 += SEG) {
-    const int seg_n = min(SEG, n_queue_items - seg0);
-    __syncthreads();
-    for (int i = tid; i < seg_n; i += 256) {
-      const int it = seg0 + i;
-      int bhx, qbx;
-      if (it < my_dense) {
-        const int d = q + it * da.n_queues;
-        bhx = d / da.dense_per_bh;
-        qbx = da.dense_first + d % da.dense_per_bh;
-      } else {
-        const int v = it - my_dense;
-        bhx = v / per_head;
-        const int pos = p0 + v % per_head;
-        qbx = a.row_order ? a.row_order[(size_t)bhx * dm.n + pos] : pos;
-      }
-      const bool sp = !dense_all && qbx < dm.n;
-      rec[i] = bhx * RSA_MAX_BLOCKS + qbx;
-      len[i] = (sp ? list_length(a, dm, (size_t)bhx * dm.n + qbx) : dm.m) * SPB;
-    }
-    __syncthreads();
-    if (tid < 64) {
-      int next = 0;
-      while (next < seg_n) {
-        const bool can = slot_ok && cnt < da.cap;
-        const int lightest = wave_min_i32(can ? load : 0x7fffffff);
-        bool take = can && load < lightest + len[next];
-        if (n_queue_items - (seg0 + next) <= kStrictTail) {
-          // the last items go one at a time to the lightest slot, so that the loads end within one item
-          const unsigned long long lightest_ones = __ballot(can && load == lightest);
-          take = lightest_ones != 0 && lane == __builtin_ctzll(lightest_ones);
-        }
-        const unsigned long long takers = __ballot(take);
-        const int mine = next + __builtin_amdgcn_mbcnt_hi((uint32_t)(takers >> 32), __builtin_amdgcn_mbcnt_lo((uint32_t)takers, 0));
-        if (take && mine < seg_n) {
-          da.table[(size_t)slot * da.cap + cnt] = rec[mine];
-          load += len[mine];
-          cnt += 1;
-        }
-        if (takers == 0) break;            // cannot happen while the table has room (the lightest slot always takes)
-        next += __popcll(takers);
-      }
-    }
-  }
-  if (tid < 64) {
-    da.nitems[slot] = cnt;
-    da.total[slot] = load;
-  }
-}
-
-template <int SPB>
-__global__ __launch_bounds__(256) void schedule_kernel(Dims dm, AttnArgs a, DealArgs da) {
-  extern __shared__ uint32_t side_lds[];
-  deal_queue<SPB>(dm, a, da, blockIdx.x, side_lds);
-}
-
-// Both of the above in one launch (neither needs the other's result, and the few workgroups that deal
-// the queues would otherwise have the chip to themselves): plane 0 of the grid deals queue blockIdx.x,
-// plane 1 + bh compensates the rows of (batch, head) bh. The dealing workgroups are dispatched first.
-template <int D, int SPB>
-__global__ __launch_bounds__(256) void compensation_schedule_kernel(Dims dm, AttnArgs a, DealArgs da) {
-  extern __shared__ uint32_t side_lds[];
-  if (blockIdx.y == 0) {
-    if ((int)blockIdx.x < da.n_queues) deal_queue<SPB>(dm, a, da, blockIdx.x, side_lds);   // uniform over the workgroup
-    return;
-  }
-  compensate_rows<D>(dm, a, blockIdx.x * 4, (int)blockIdx.y - 1, side_lds);
-}
-
-// Sizes of the schedule for `n_wg` resident workgroups of NGRP groups (host and launcher agree on them).
-struct SchedShape {
-  int n_queues, slots_per_xcd, cap, chunk, n_items, n_dense, dense_per_bh, dense_first;
-};
-inline SchedShape sched_shape(const Dims& dm, int flags, int n_wg, int ngrp) {
-  SchedShape s;
-  const bool dense_all = (flags & RSA_DENSE) != 0;
-  const int bh = dm.batch * dm.heads;
-  s.slots_per_xcd = (n_wg / 8) * ngrp;
-  s.n_queues = 8 * ((s.slots_per_xcd + 63) / 64);
-  s.dense_per_bh = dense_all ? dm.m : dm.mt;
-  s.dense_first = dense_all ? 0 : dm.n;
-  s.n_dense = bh * s.dense_per_bh;
-  s.n_items = s.n_dense + (dense_all ? 0 : bh * dm.n);
-  s.chunk = (dm.n + s.n_queues - 1) / s.n_queues;
-  const long long longest = (s.n_dense + s.n_queues - 1) / s.n_queues + (dense_all ? 0LL : (long long)bh * s.chunk);
-  // room for twice the average share of a slot, so that a queue of very unequal items still balances;
-  // the last queue of an XCD may have fewer than 64 slots
-  const int fewest = s.slots_per_xcd % 64 ? s.slots_per_xcd % 64 : 64;
-  s.cap = (int)(2 * ((longest + fewest - 1) / fewest) + 8);
-  return s;
-}
-
 template <int D, int BLK>
 hipError_t launch_attn_t(const Dims& dm, const AttnArgs& a, const AttnSched& ws, hipStream_t s) {
   using C = AttnCfg<D, BLK>;
-  const int bh = dm.batch * dm.heads;
   const bool dense_all = (a.flags & RSA_DENSE) != 0;
   const int n_wg = ws.n_wg;
   if (n_wg < 8 || n_wg % 8) return hipErrorInvalidValue;
@@ -1182,26 +912,15 @@ hipError_t launch_attn_t(const Dims& dm, const AttnArgs& a, const AttnSched& ws,
   sc.dense_first = sh.dense_first;
   const bool compensate = !dense_all && (a.flags & RSA_COMPENSATE);
   const bool deal = ws.table && sh.n_queues * 64 <= RSA_ATTN_SCHED_SLOTS && (size_t)sh.n_queues * 64 * sh.cap <= ws.table_entries;
-  const dim3 comp_grid((dm.n + 3) / 4, bh);
-  const unsigned comp_lds = 4u * (unsigned)((dm.m + 63) / 64) * 64u * 2u;    // four lists of 16-bit block indices
-  const unsigned deal_lds = 2u * kDealSegment * 4u;
-  if (!dense_all && a.row_order) hipLaunchKernelGGL(row_order_kernel, dim3(bh), dim3(1024), 0, s, dm, a);
+  DealArgs da = {};
   if (deal) {
-    DealArgs da;
     da.table = ws.table; da.nitems = ws.nitems; da.total = ws.total;
     da.cap = sh.cap; da.n_queues = sh.n_queues; da.slots_per_xcd = sh.slots_per_xcd;
     da.n_dense = sh.n_dense; da.dense_per_bh = sc.dense_per_bh; da.dense_first = sh.dense_first;
-    if (compensate && sh.n_queues <= (int)comp_grid.x)
-      hipLaunchKernelGGL((compensation_schedule_kernel<D, C::SPB>), dim3(comp_grid.x, bh + 1), dim3(256),
-                         comp_lds > deal_lds ? comp_lds : deal_lds, s, dm, a, da);
-    else {
-      if (compensate) hipLaunchKernelGGL((compensation_kernel<D>), comp_grid, dim3(256), comp_lds, s, dm, a);
-      hipLaunchKernelGGL((schedule_kernel<C::SPB>), dim3(sh.n_queues), dim3(256), deal_lds, s, dm, a, da);
-    }
     sc.table = ws.table; sc.nitems = ws.nitems; sc.total = ws.total; sc.cap = sh.cap;
-  } else if (compensate) {
-    hipLaunchKernelGGL((compensation_kernel<D>), comp_grid, dim3(256), comp_lds, s, dm, a);
   }
+  const hipError_t side = launch_attn_side(dm, a, da, !dense_all && a.row_order, compensate, deal, C::SPB, s);
+  if (side != hipSuccess) return side;
   hipLaunchKernelGGL((attn_kernel<D, BLK>), dim3((unsigned)n_wg), dim3(C::NTHR), 0, s, dm, a, sc);
   return hipGetLastError();
 }
