@@ -6,6 +6,7 @@
 // flight before the first add. Algorithmic traffic: 2 bytes read per input element, plus
 // 2 bytes written per V element for the channel-major copy.
 #include "rsa_common.hpp"
+#include "text_mass.hpp"
 
 namespace rsa {
 namespace {
@@ -69,15 +70,21 @@ __global__ __launch_bounds__(256) void pool_qk_kernel(Dims dm, PoolArgs a) {
 // channel row holds token 16c + 8g + 4h + e of the block (the two middle groups of four
 // swapped in every run of 16), which is the order in which one half-wave holds the
 // softmax probabilities after the S^T = K Q^T product; tokens past the block end are 0.
+// LDS: 256 / (D/8) rows of D floats for the mean, then BLK rows of D/2 + 1 words for the tile.
 template <int D, int BLK>
-__global__ __launch_bounds__(256) void pool_v_kernel(Dims dm, PoolArgs a) {
+struct PoolVLds {
+  static constexpr int TS = D / 2 + 1;          // tile row stride in 32-bit words (odd: spreads rows over banks)
+  static constexpr int RED = (256 / (D / 8)) * D;
+  static constexpr int WORDS = RED + BLK * TS;
+};
+template <int D, int BLK>
+__device__ __forceinline__ void pool_v_block(const Dims& dm, const PoolArgs& a, int m, int bh, uint32_t* lds) {
   constexpr int CPR = D / 8;
   constexpr int RPP = 256 / CPR;
   constexpr int NPASS = BLK / RPP;
-  constexpr int TS = D / 2 + 1;  // tile row stride in 32-bit words (odd: spreads rows over banks)
-  __shared__ float red[RPP][D];
-  __shared__ uint32_t tile[BLK * TS];
-  const int m = blockIdx.x, bh = blockIdx.y;
+  constexpr int TS = PoolVLds<D, BLK>::TS;
+  float (*red)[D] = reinterpret_cast<float (*)[D]>(lds);
+  uint32_t* tile = lds + PoolVLds<D, BLK>::RED;
   const int b = bh / dm.heads, h = bh % dm.heads;
   const uint16_t* X = a.V + (int64_t)b * dm.sb + (int64_t)h * dm.sh;
   const int64_t t0 = dm.block_start(m);
@@ -122,11 +129,38 @@ __global__ __launch_bounds__(256) void pool_v_kernel(Dims dm, PoolArgs a) {
 }
 
 template <int D, int BLK>
+__global__ __launch_bounds__(256) void pool_v_kernel(Dims dm, PoolArgs a) {
+  __shared__ uint32_t lds[PoolVLds<D, BLK>::WORDS];
+  pool_v_block<D, BLK>(dm, a, blockIdx.x, blockIdx.y, lds);
+}
+
+// The same launch with the text log-masses on board: the first `text_wgs` workgroups of every
+// (batch, head) take eight pooled queries each against the text keys (vector-ALU work, no traffic to
+// speak of), the others pool a block of V (HBM-bound) -- the one hides under the other.
+template <int D, int BLK>
+__global__ __launch_bounds__(256) void pool_v_text_kernel(Dims dm, PoolArgs a, ScoreArgs sa, int text_wgs) {
+  constexpr int WORDS = PoolVLds<D, BLK>::WORDS > text_mass_lds_floats<D>() ? PoolVLds<D, BLK>::WORDS : text_mass_lds_floats<D>();
+  __shared__ uint32_t lds[WORDS];
+  if ((int)blockIdx.x < text_wgs) {          // the whole workgroup
+    text_mass_block<D, BLK>(dm, sa, blockIdx.x * kTextMassQueries, blockIdx.y, reinterpret_cast<float*>(lds));
+    return;
+  }
+  pool_v_block<D, BLK>(dm, a, (int)blockIdx.x - text_wgs, blockIdx.y, lds);
+}
+
+template <int D, int BLK>
 hipError_t launch_pool_t(const Dims& dm, const PoolArgs& a, hipStream_t s) {
   const dim3 block(256);
   if (a.Q && a.K)    // values only: the caller keeps the pooled queries / keys of an earlier call
     hipLaunchKernelGGL((pool_qk_kernel<D, BLK>), dim3(dm.m, dm.batch * dm.heads, a.skip_k ? 1 : 2), block, 0, s, dm, a);
-  hipLaunchKernelGGL((pool_v_kernel<D, BLK>), dim3(dm.m, dm.batch * dm.heads, 1), block, 0, s, dm, a);
+  if (a.text_K && a.text_Lmass && a.Q && dm.tt > 0) {   // Qp is written by the launch above
+    ScoreArgs sa = {};
+    sa.K = a.text_K; sa.Qp = a.Qp; sa.Lmass = a.text_Lmass;
+    const int text_wgs = (dm.n + kTextMassQueries - 1) / kTextMassQueries;
+    hipLaunchKernelGGL((pool_v_text_kernel<D, BLK>), dim3(dm.m + text_wgs, dm.batch * dm.heads, 1), block, 0, s, dm, a, sa, text_wgs);
+  } else {
+    hipLaunchKernelGGL((pool_v_kernel<D, BLK>), dim3(dm.m, dm.batch * dm.heads, 1), block, 0, s, dm, a);
+  }
   return hipGetLastError();
 }
 

@@ -203,6 +203,7 @@ int rsa_pool(const rsa_shape* shape, const void* Q, const void* K, const void* V
   pa.Kpb = (uint16_t*)(wsb + wl.kpb);
   // with the gate on, the launch that reads the key blocks for their deviations pools them as well
   pa.skip_k = gapr_mode == 1;
+  pa.text_K = (const uint16_t*)K; pa.text_Lmass = Lmass;     // the text log-masses ride with the pooling of V
   if (rsa::launch_pool(d, pa, s) != hipSuccess) return RSA_E_LAUNCH;
 
   rsa::GaprArgs ga;
@@ -219,6 +220,7 @@ int rsa_pool(const rsa_shape* shape, const void* Q, const void* K, const void* V
   rsa::ScoreArgs sa;
   sa.K = (const uint16_t*)K; sa.Qp = Qp; sa.Kp = Kp;
   sa.Spool = Spool; sa.Apool = Apool; sa.Lmass = Lmass;
+  sa.text_done = true;
   if (rsa::launch_scores(d, sa, s) != hipSuccess) return RSA_E_LAUNCH;
 
   if (gapr_mode == 1) {

@@ -82,6 +82,10 @@ struct PoolArgs {
   uint16_t* Vt;
   uint16_t *Qpb, *Kpb;     // optional fp16 copies of the pooled vectors in gate_operand_offset layout
   bool skip_k = false;     // the pooled keys come from the key-side launch of the gate (launch_gapr_keys)
+  // when both are set (and Q is pooled by this call: the pooled queries are needed), the launch that pools V also
+  // writes the text columns of Lmass from the text keys of text_K
+  const uint16_t* text_K = nullptr;
+  float* text_Lmass = nullptr;
 };
 hipError_t launch_pool(const Dims& dm, const PoolArgs& a, hipStream_t s);
 
@@ -89,6 +93,7 @@ struct ScoreArgs {
   const uint16_t* K;
   const float *Qp, *Kp;
   float *Spool, *Apool, *Lmass;
+  bool text_done = false;  // the text columns of Lmass are already written (by the launch that pooled V)
 };
 hipError_t launch_scores(const Dims& dm, const ScoreArgs& a, hipStream_t s);
 

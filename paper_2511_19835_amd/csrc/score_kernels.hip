@@ -15,6 +15,7 @@
 
 #include "lds_dma.hpp"
 #include "rsa_common.hpp"
+#include "text_mass.hpp"
 
 namespace rsa {
 namespace {
@@ -88,68 +89,11 @@ __global__ __launch_bounds__(256) void pooled_scores_kernel(Dims dm, ScoreArgs a
   }
 }
 
-// Eight pooled queries per workgroup against the individual text keys, 256 tokens at a
-// time (a multiple of the block size), then one log-sum-exp per (query, text block).
+// The text log-masses by themselves (text_mass.hpp has the work).
 template <int D, int BLK>
 __global__ __launch_bounds__(256) void text_mass_kernel(Dims dm, ScoreArgs a) {
-  constexpr int NQ = 8;
-  __shared__ float qs[NQ][D];
-  __shared__ float u[NQ][256];
-  const int bh = blockIdx.y;
-  const int b = bh / dm.heads, h = bh % dm.heads;
-  const int n0 = blockIdx.x * NQ;
-  const float* Qp = a.Qp + (size_t)bh * dm.n * D;
-  for (int idx = threadIdx.x; idx < NQ * D; idx += 256) {
-    const int r = idx / D, c = idx % D;
-    qs[r][c] = (n0 + r < dm.n) ? Qp[(size_t)(n0 + r) * D + c] : 0.f;
-  }
-  __syncthreads();
-  const uint16_t* Kt = a.K + (int64_t)b * dm.sb + (int64_t)h * dm.sh + dm.tv * dm.st;
-  float* L = a.Lmass + (size_t)bh * dm.n * dm.m;
-  const int wave = threadIdx.x / 64, lane = threadIdx.x % 64;
-
-  for (int64_t c0 = 0; c0 < dm.tt; c0 += 256) {
-    const int64_t tok = c0 + threadIdx.x;
-    float acc[NQ];
-#pragma unroll
-    for (int r = 0; r < NQ; ++r) acc[r] = 0.f;
-    if (tok < dm.tt) {
-      const uint4* row = reinterpret_cast<const uint4*>(Kt + tok * dm.st);
-#pragma unroll 4
-      for (int cc = 0; cc < D / 8; ++cc) {
-        const uint4 v = row[cc];
-        const uint32_t w[4] = {v.x, v.y, v.z, v.w};
-#pragma unroll
-        for (int i = 0; i < 4; ++i) {
-          const float k0 = bf16_bits_to_float(w[i] & 0xffffu), k1 = bf16_bits_to_float(w[i] >> 16);
-#pragma unroll
-          for (int r = 0; r < NQ; ++r) {
-            acc[r] = fmaf(qs[r][cc * 8 + 2 * i], k0, acc[r]);
-            acc[r] = fmaf(qs[r][cc * 8 + 2 * i + 1], k1, acc[r]);
-          }
-        }
-      }
-    }
-#pragma unroll
-    for (int r = 0; r < NQ; ++r) u[r][threadIdx.x] = acc[r] * dm.scale;
-    __syncthreads();
-    // tasks: (query r, block j of this chunk); one wave per task
-    constexpr int BPC = 256 / BLK;
-    for (int task = wave; task < NQ * BPC; task += 4) {
-      const int r = task / BPC, j = task % BPC;
-      const int64_t first = c0 + (int64_t)j * BLK;
-      if (first >= dm.tt || n0 + r >= dm.n) continue;
-      const int cnt = (int)((dm.tt - first) < BLK ? (dm.tt - first) : BLK);
-      float mx = -INFINITY;
-      for (int i = lane; i < cnt; i += 64) mx = fmaxf(mx, u[r][j * BLK + i]);
-      mx = wave_max(mx);
-      float sum = 0.f;
-      for (int i = lane; i < cnt; i += 64) sum += expf(u[r][j * BLK + i] - mx);
-      sum = wave_sum(sum);
-      if (lane == 0) L[(size_t)(n0 + r) * dm.m + dm.n + (int)(first / BLK)] = mx + logf(sum);
-    }
-    __syncthreads();
-  }
+  __shared__ float lds[text_mass_lds_floats<D>()];
+  text_mass_block<D, BLK>(dm, a, blockIdx.x * kTextMassQueries, blockIdx.y, lds);
 }
 
 // One wave per row, the row held in registers (rows of at most 64 * NI blocks), so every value
@@ -456,7 +400,7 @@ hipError_t launch_scores_t(const Dims& dm, const ScoreArgs& a, hipStream_t s) {
   const int bh = dm.batch * dm.heads;
   if (dm.m <= 1024) {
     // rows short enough for the registers of a workgroup: the text log-masses first, then one pass
-    if (dm.tt > 0)
+    if (dm.tt > 0 && !a.text_done)
       hipLaunchKernelGGL((text_mass_kernel<D, BLK>), dim3((dm.n + 7) / 8, bh), dim3(256), 0, s, dm, a);
     const dim3 fgrid(8 * ((bh + 7) / 8) * ((dm.n + 31) / 32));
     if (dm.m <= 256)
@@ -468,7 +412,7 @@ hipError_t launch_scores_t(const Dims& dm, const ScoreArgs& a, hipStream_t s) {
     return hipGetLastError();
   }
   hipLaunchKernelGGL((pooled_scores_kernel<D>), dim3((dm.m + 63) / 64, (dm.n + 63) / 64, bh), dim3(256), 0, s, dm, a);
-  if (dm.tt > 0)
+  if (dm.tt > 0 && !a.text_done)
     hipLaunchKernelGGL((text_mass_kernel<D, BLK>), dim3((dm.n + 7) / 8, bh), dim3(256), 0, s, dm, a);
   const dim3 rgrid((dm.n + 3) / 4, bh);
   if (dm.m <= 64 * 4)
