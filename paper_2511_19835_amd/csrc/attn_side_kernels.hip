@@ -11,8 +11,8 @@ namespace {
 // W V^pool with W[n][m] = A^pool[n][m] where block m is compensated for row n and 0 elsewhere
 // (about a fifth of the entries at the benchmark shape), on v_mfma_f32_32x32x2_f32 -- fp32 operands,
 // fp32 products and sums. One workgroup per 32 query blocks of a (batch, head); the key blocks come
-// 64 at a time: the weights of the 32 rows (masked while they are read; rows of A^pool are only read
-// where a bit is set) and the 64 rows of v^pool go through LDS, the next 64 are on their way while
+// 64 at a time: the weights of the 32 rows (read whole, masked on their way into LDS) and the 64 rows
+// of v^pool go through LDS, the next 64 are on their way while
 // the matrix instructions of these run; wave w owns channels 32 w .. 32 w + 31 (M = query row,
 // N = channel, k = key block: the lower half-wave takes blocks 8u .. 8u+3 of a run of eight, the
 // upper one 8u+4 .. 8u+7, both operands alike). Blocks past the end of the row carry weight 0.
@@ -40,13 +40,26 @@ __device__ __forceinline__ void compensate_tile(const Dims& dm, const AttnArgs& 
   const uint32_t* gate = a.Mc_bits + row * dm.w;
   const float* A = a.Apool + row * dm.m;
   float w[8];
+  uint32_t on = 0u;                              // bits of this thread's eight blocks: compensated or not
   floatx4 vv[VL];
+  typedef float floatx4_u __attribute__((ext_vector_type(4), aligned(4)));     // rows of A^pool start at any word
+  // Nothing here depends on anything else loaded here: the weights are read whole and masked when they go to LDS.
   auto fetch = [&](int m0) __attribute__((always_inline)) {
     const int m = m0 + wc;
-    uint32_t on = 0u;
-    if (row_ok && m < dm.m) on = (~kept[m / 32] & gate[m / 32]) >> (m % 32);
+    on = 0u;
 #pragma unroll
-    for (int e = 0; e < 8; ++e) w[e] = (((on >> e) & 1u) && m + e < dm.m) ? A[m + e] : 0.f;
+    for (int e = 0; e < 8; ++e) w[e] = 0.f;
+    if (row_ok && m < dm.m) {
+      on = (~kept[m / 32] & gate[m / 32]) >> (m % 32);
+      if (m + 8 <= dm.m) {
+        const floatx4 lo = *reinterpret_cast<const floatx4_u*>(A + m), hi = *reinterpret_cast<const floatx4_u*>(A + m + 4);
+#pragma unroll
+        for (int e = 0; e < 4; ++e) { w[e] = lo[e]; w[4 + e] = hi[e]; }
+      } else {
+#pragma unroll
+        for (int e = 0; e < 8; ++e) if (m + e < dm.m) w[e] = A[m + e];
+      }
+    }
 #pragma unroll
     for (int i = 0; i < VL; ++i) {
       const int idx = tid + 256 * i, r = idx / (D / 4), c4 = idx % (D / 4);
@@ -60,6 +73,8 @@ __device__ __forceinline__ void compensate_tile(const Dims& dm, const AttnArgs& 
   fetch(0);
   for (int m0 = 0; m0 < dm.m; m0 += MC) {
     __syncthreads();                             // the tiles of the pass before have been read
+#pragma unroll
+    for (int e = 0; e < 8; ++e) w[e] = ((on >> e) & 1u) ? w[e] : 0.f;
     *reinterpret_cast<floatx4*>(wt + wr * AS + wc) = floatx4{w[0], w[1], w[2], w[3]};
     *reinterpret_cast<floatx4*>(wt + wr * AS + wc + 4) = floatx4{w[4], w[5], w[6], w[7]};
 #pragma unroll
